@@ -1,0 +1,125 @@
+/*
+ * libinvact -- Inverted Activations (arXiv 2407.15545) for AMD MI355X (gfx950).
+ *
+ * C ABI of the element-wise hot path: a GELU / SiLU layer that saves its OUTPUT
+ * and a 1-bit-per-element branch mask instead of its input, and rebuilds
+ * f'(x) in the backward pass from the saved output with the paper's
+ * closed-form approximation of f'(f^-1(y)).
+ *
+ * Conventions shared by every compute entry point
+ *   - All data pointers are DEVICE pointers owned by the caller.  The library
+ *     never allocates, frees, copies to the host or synchronises.
+ *   - Work is enqueued on `stream` (0 = the default stream); the call returns
+ *     as soon as the kernel is launched.
+ *   - Tensors are flat and contiguous, `n` elements each; shape is the caller's
+ *     business.  dtype selects the storage format of every floating-point
+ *     tensor of the call (arithmetic is binary32 in registers, one
+ *     round-to-nearest-even at the store).
+ *   - `mask` holds invact_mask_bytes(n) bytes: element i is bit (i mod 8) of
+ *     byte (i div 8), i.e. bit (i mod 64) of little-endian 64-bit word
+ *     (i div 64) (Method, "Space-efficient Boolean Indicator").  The forward
+ *     entry points write every byte of it; bits past n are written as 0.
+ *   - Floating-point pointers must be 16-byte aligned and `mask` 8-byte
+ *     aligned, else INVACT_ERR_ALIGN.
+ *   - Element-wise aliasing of an output with an input of the same call and
+ *     the same dtype is allowed (y == x, grad_x == grad_y, grad_up == grad_h,
+ *     grad_gate == grad_h, ...); any other overlap is undefined.
+ *   - The return value is an invact_status (0 = success).  n == 0 succeeds
+ *     without a launch.  Arguments are validated before anything is enqueued.
+ *   - Calls are thread-safe; the library keeps no mutable state apart from the
+ *     tuning parameters below.
+ */
+#ifndef INVACT_H
+#define INVACT_H
+
+#include <stddef.h>
+#include <hip/hip_runtime_api.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    INVACT_GELU_TANH = 0,   /* x (1 + tanh(sqrt(2/pi) (x + 0.044715 x^3))) / 2 */
+    INVACT_GELU_ERF  = 1,   /* x Phi(x)                                        */
+    INVACT_SILU      = 2    /* x sigmoid(x)                                    */
+} invact_kind;
+
+typedef enum { INVACT_FP32 = 0, INVACT_BF16 = 1 } invact_dtype;
+
+typedef enum {
+    INVACT_OK = 0,
+    INVACT_ERR_KIND,        /* kind is not an invact_kind                      */
+    INVACT_ERR_DTYPE,       /* dtype is not an invact_dtype                    */
+    INVACT_ERR_NULL,        /* a required pointer is NULL (and n > 0)          */
+    INVACT_ERR_ALIGN,       /* a pointer is not aligned as required            */
+    INVACT_ERR_SIZE,        /* n is too large for the mask size to fit size_t  */
+    INVACT_ERR_HIP          /* the HIP runtime refused the launch              */
+} invact_status;
+
+/* Bytes of the mask of an n-element tensor: 8 * ceil(n / 64). */
+size_t invact_mask_bytes(size_t n);
+
+/* Static, human-readable text for a status code. */
+const char* invact_strerror(int status);
+
+/*
+ * Forward of the layer (Algorithm 1, forward; Eq. (1), Eq. (4)):
+ *   y[i] = f(x[i]),  mask bit i = (x[i] < T),  T = the minimiser of f.
+ * x: in, n elements.  y: out, n elements.  mask: out, invact_mask_bytes(n).
+ * x == T and NaN give bit 0; f(-inf) = -0 with bit 1.
+ */
+int invact_fwd(int kind, int dtype, const void* x, void* y, void* mask,
+               size_t n, hipStream_t stream);
+
+/*
+ * Backward of the layer (Algorithm 1, backward; Eqs. (5)-(8)):
+ *   grad_x[i] = grad_y[i] * q(y[i], s_i),
+ * q = q_left if the mask bit s_i is 1 else q_right, with the coefficients of
+ * the appendix "Approximation Coefficients".  Square-root arguments are
+ * clamped at 0; q(+inf, 0) = 1; NaN in y or grad_y gives NaN.
+ * y, grad_y: in.  mask: in, as written by invact_fwd.  grad_x: out.
+ */
+int invact_bwd(int kind, int dtype, const void* y, const void* mask,
+               const void* grad_y, void* grad_x, size_t n, hipStream_t stream);
+
+/*
+ * Gated block, forward (Experiments, "GeGLU" block; Limitations: the product
+ * saves the activation's output anyway):
+ *   act[i] = f(gate[i]),  mask bit i = (gate[i] < T),  h[i] = f(gate[i]) * up[i]
+ * (h is formed from the unrounded activation).  The block saves act, up, mask.
+ * gate, up: in.  act, h: out.  mask: out.
+ * swiglu_invact_fwd is geglu_invact_fwd with kind = INVACT_SILU.
+ */
+int geglu_invact_fwd(int kind, int dtype, const void* gate, const void* up,
+                     void* act, void* h, void* mask, size_t n, hipStream_t stream);
+int swiglu_invact_fwd(int dtype, const void* gate, const void* up,
+                      void* act, void* h, void* mask, size_t n, hipStream_t stream);
+
+/*
+ * Gated block, backward from the saved tensors (Algorithm 1, backward, applied
+ * to the activation inside the product):
+ *   grad_up[i]   = grad_h[i] * act[i]
+ *   grad_gate[i] = grad_h[i] * up[i] * q(act[i], s_i)
+ * act, up, grad_h: in.  mask: in.  grad_gate, grad_up: out.
+ * swiglu_invact_bwd is geglu_invact_bwd with kind = INVACT_SILU.
+ */
+int geglu_invact_bwd(int kind, int dtype, const void* act, const void* up,
+                     const void* mask, const void* grad_h,
+                     void* grad_gate, void* grad_up, size_t n, hipStream_t stream);
+int swiglu_invact_bwd(int dtype, const void* act, const void* up,
+                      const void* mask, const void* grad_h,
+                      void* grad_gate, void* grad_up, size_t n, hipStream_t stream);
+
+/*
+ * Launch tuning (process-wide, for benchmarking): number of 256-thread
+ * workgroups per compute unit the grid-stride kernels are launched with.
+ * 0 restores the built-in default.  Returns the value now in force, or a
+ * negative number if `blocks_per_cu` is out of range (0..64).
+ */
+int invact_set_blocks_per_cu(int blocks_per_cu);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* INVACT_H */

@@ -1,0 +1,168 @@
+"""ctypes binding of libinvact.so: argument marshalling only.
+
+Every step of the path runs in the library's HIP kernels.  PyTorch supplies
+device memory (tensors) and streams, nothing else; there is no fallback: if the
+library is missing, loading it raises.
+"""
+import ctypes
+import os
+
+import torch
+
+KINDS = {"gelu_tanh": 0, "gelu_erf": 1, "silu": 2}
+DTYPES = {torch.float32: 0, torch.bfloat16: 1}
+DTYPE_NAMES = {"fp32": torch.float32, "bf16": torch.bfloat16}
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libinvact.so")
+_lib = None
+
+_vp, _sz, _int = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+_PROTOTYPES = {
+    "invact_mask_bytes": (_sz, [_sz]),
+    "invact_strerror": (ctypes.c_char_p, [_int]),
+    "invact_set_blocks_per_cu": (_int, [_int]),
+    "invact_fwd": (_int, [_int, _int, _vp, _vp, _vp, _sz, _vp]),
+    "invact_bwd": (_int, [_int, _int, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "geglu_invact_fwd": (_int, [_int, _int, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "geglu_invact_bwd": (_int, [_int, _int, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "swiglu_invact_fwd": (_int, [_int, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "swiglu_invact_bwd": (_int, [_int, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+}
+
+
+class InvactError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__(f"libinvact: {message} (status {status})")
+        self.status = status
+
+
+def lib():
+    """The loaded library with prototypes declared (raises if it is not built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError(
+                f"{_LIB_PATH} is missing: build it with `python -m paper_2407_15545_amd.build` "
+                "(there is no fallback implementation)")
+        handle = ctypes.CDLL(_LIB_PATH)
+        for name, (res, args) in _PROTOTYPES.items():
+            fn = getattr(handle, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = handle
+    return _lib
+
+
+def strerror(status):
+    return lib().invact_strerror(status).decode()
+
+
+def _check(status):
+    if status != 0:
+        raise InvactError(status, strerror(status))
+
+
+def _kind(kind):
+    return KINDS[kind] if isinstance(kind, str) else int(kind)
+
+
+def _stream(stream):
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _tensors(*ts):
+    first = ts[0]
+    for t in ts:
+        if not (t.is_cuda and t.is_contiguous()):
+            raise ValueError("tensors must be contiguous CUDA tensors")
+        if t.dtype != first.dtype or t.numel() != first.numel() or t.device != first.device:
+            raise ValueError("tensors of one call must share dtype, element count and device")
+    if first.dtype not in DTYPES:
+        raise ValueError(f"unsupported dtype {first.dtype}")
+    return DTYPES[first.dtype], first.numel()
+
+
+def _mask_arg(mask, n, like):
+    nbytes = mask_bytes(n)
+    if mask is None:
+        return torch.empty(nbytes, dtype=torch.uint8, device=like.device)
+    if mask.dtype != torch.uint8 or mask.numel() < nbytes or not mask.is_contiguous() or mask.device != like.device:
+        raise ValueError(f"mask must be a contiguous uint8 tensor of >= {nbytes} bytes on the same device")
+    return mask
+
+
+def mask_bytes(n):
+    return int(lib().invact_mask_bytes(n))
+
+
+def set_blocks_per_cu(v):
+    return int(lib().invact_set_blocks_per_cu(int(v)))
+
+
+def invact_fwd(kind, x, y=None, mask=None, stream=None):
+    """y = f(x) and the packed branch mask.  Returns (y, mask)."""
+    y = torch.empty_like(x) if y is None else y
+    dt, n = _tensors(x, y)
+    mask = _mask_arg(mask, n, x)
+    with torch.cuda.device(x.device):
+        _check(lib().invact_fwd(_kind(kind), dt, x.data_ptr(), y.data_ptr(), mask.data_ptr(), n, _stream(stream)))
+    return y, mask
+
+
+def invact_bwd(kind, y, mask, grad_y, grad_x=None, stream=None):
+    """grad_x = grad_y * q(y, mask).  Returns grad_x."""
+    grad_x = torch.empty_like(grad_y) if grad_x is None else grad_x
+    dt, n = _tensors(y, grad_y, grad_x)
+    mask = _mask_arg(mask, n, y)
+    with torch.cuda.device(y.device):
+        _check(lib().invact_bwd(_kind(kind), dt, y.data_ptr(), mask.data_ptr(), grad_y.data_ptr(),
+                                grad_x.data_ptr(), n, _stream(stream)))
+    return grad_x
+
+
+def geglu_invact_fwd(kind, gate, up, act=None, h=None, mask=None, stream=None):
+    """act = f(gate), h = f(gate) * up and the mask.  Returns (act, h, mask)."""
+    act = torch.empty_like(gate) if act is None else act
+    h = torch.empty_like(gate) if h is None else h
+    dt, n = _tensors(gate, up, act, h)
+    mask = _mask_arg(mask, n, gate)
+    with torch.cuda.device(gate.device):
+        _check(lib().geglu_invact_fwd(_kind(kind), dt, gate.data_ptr(), up.data_ptr(), act.data_ptr(),
+                                      h.data_ptr(), mask.data_ptr(), n, _stream(stream)))
+    return act, h, mask
+
+
+def geglu_invact_bwd(kind, act, up, mask, grad_h, grad_gate=None, grad_up=None, stream=None):
+    """grad_up = grad_h * act, grad_gate = grad_h * up * q(act, mask).  Returns (grad_gate, grad_up)."""
+    grad_gate = torch.empty_like(act) if grad_gate is None else grad_gate
+    grad_up = torch.empty_like(act) if grad_up is None else grad_up
+    dt, n = _tensors(act, up, grad_h, grad_gate, grad_up)
+    mask = _mask_arg(mask, n, act)
+    with torch.cuda.device(act.device):
+        _check(lib().geglu_invact_bwd(_kind(kind), dt, act.data_ptr(), up.data_ptr(), mask.data_ptr(),
+                                      grad_h.data_ptr(), grad_gate.data_ptr(), grad_up.data_ptr(), n,
+                                      _stream(stream)))
+    return grad_gate, grad_up
+
+
+def swiglu_invact_fwd(gate, up, act=None, h=None, mask=None, stream=None):
+    act = torch.empty_like(gate) if act is None else act
+    h = torch.empty_like(gate) if h is None else h
+    dt, n = _tensors(gate, up, act, h)
+    mask = _mask_arg(mask, n, gate)
+    with torch.cuda.device(gate.device):
+        _check(lib().swiglu_invact_fwd(dt, gate.data_ptr(), up.data_ptr(), act.data_ptr(), h.data_ptr(),
+                                       mask.data_ptr(), n, _stream(stream)))
+    return act, h, mask
+
+
+def swiglu_invact_bwd(act, up, mask, grad_h, grad_gate=None, grad_up=None, stream=None):
+    grad_gate = torch.empty_like(act) if grad_gate is None else grad_gate
+    grad_up = torch.empty_like(act) if grad_up is None else grad_up
+    dt, n = _tensors(act, up, grad_h, grad_gate, grad_up)
+    mask = _mask_arg(mask, n, act)
+    with torch.cuda.device(act.device):
+        _check(lib().swiglu_invact_bwd(dt, act.data_ptr(), up.data_ptr(), mask.data_ptr(), grad_h.data_ptr(),
+                                       grad_gate.data_ptr(), grad_up.data_ptr(), n, _stream(stream)))
+    return grad_gate, grad_up

@@ -1,0 +1,37 @@
+"""Builds libinvact.so (the HIP kernels and their C ABI) for gfx950, in-tree."""
+import os
+import subprocess
+import sys
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+SRC = os.path.join(HERE, "csrc", "invact_kernels.hip")
+DEPS = [SRC, os.path.join(HERE, "csrc", "invact_math.h"), os.path.join(HERE, "csrc", "invact_constants.h"),
+        os.path.join(os.path.dirname(HERE), "include", "invact.h")]
+LIB = os.path.join(HERE, "libinvact.so")
+
+HIPCC_FLAGS = [
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    # hipcc must not form packed-FP32 instructions on this target
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-Wall", "-Wextra", "-Wno-unused-command-line-argument",
+]
+
+
+def up_to_date():
+    return os.path.exists(LIB) and all(os.path.getmtime(LIB) >= os.path.getmtime(d) for d in DEPS)
+
+
+def build(force=True, verbose=False, extra=()):
+    """Compile the library.  Returns its path."""
+    if not force and up_to_date():
+        return LIB
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, *HIPCC_FLAGS, *extra, "-o", LIB, SRC]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(force=True, verbose=True, extra=sys.argv[1:]))

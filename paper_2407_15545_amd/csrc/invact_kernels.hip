@@ -1,0 +1,414 @@
+// HIP kernels and C ABI of libinvact (gfx950 only).  See include/invact.h for
+// the contract of every entry point.
+//
+// Kernel shape.  All four kernels are pure streaming maps, bound by HBM
+// bandwidth, so they share one skeleton: a grid of 256-thread workgroups
+// (a few per compute unit) strides over the tensor in "chunks" of 8
+// consecutive elements per lane.  8 elements are one 128-bit access for
+// bfloat16 (two for binary32) and exactly one byte of the branch mask, so a
+// lane owns its mask byte outright: the canonical little-endian bit stream
+// comes out of lane-local shifts, no cross-lane traffic, and a wavefront
+// writes 64 consecutive mask bytes (eight 64-bit words) per step.  Each lane
+// keeps kUnroll independent chunks in flight: all loads of a step are issued
+// before the first store, which is also what makes element-wise in-place use
+// (y == x and the like) safe.  The < 8 elements past the last full chunk and
+// the zero padding of the last mask word are written by one thread.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <atomic>
+
+#include "../../include/invact.h"
+#include "invact_math.h"
+
+namespace {
+
+using namespace invact_dev;
+
+constexpr int kThreads = 256;
+constexpr int kUnroll  = 2;
+constexpr int kDefaultBlocksPerCu = 8;
+
+typedef float    f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16   bf16x2 __attribute__((ext_vector_type(2)));
+typedef float    f32x2 __attribute__((ext_vector_type(2)));
+
+// ---------------------------------------------------------------------------
+// Storage formats: 8 elements <-> 8 floats in registers
+// ---------------------------------------------------------------------------
+
+template <int DT> struct Storage;
+
+template <> struct Storage<INVACT_FP32> {
+    struct Raw { f32x4 a, b; };
+    static constexpr int kPrec = PRECISE;
+    static __device__ __forceinline__ Raw load(const void* p, size_t chunk)
+    {
+        const f32x4* q = reinterpret_cast<const f32x4*>(p) + 2 * chunk;
+        return Raw{q[0], q[1]};
+    }
+    static __device__ __forceinline__ void unpack(const Raw& r, float (&v)[8])
+    {
+        for (int j = 0; j < 4; ++j) { v[j] = r.a[j]; v[4 + j] = r.b[j]; }
+    }
+    static __device__ __forceinline__ void store(void* p, size_t chunk, const float (&v)[8])
+    {
+        f32x4* q = reinterpret_cast<f32x4*>(p) + 2 * chunk;
+        q[0] = f32x4{v[0], v[1], v[2], v[3]};
+        q[1] = f32x4{v[4], v[5], v[6], v[7]};
+    }
+    static __device__ __forceinline__ float load1(const void* p, size_t i) { return reinterpret_cast<const float*>(p)[i]; }
+    static __device__ __forceinline__ void store1(void* p, size_t i, float v) { reinterpret_cast<float*>(p)[i] = v; }
+};
+
+template <> struct Storage<INVACT_BF16> {
+    struct Raw { u32x4 w; };
+    static constexpr int kPrec = FAST;
+    static __device__ __forceinline__ Raw load(const void* p, size_t chunk)
+    {
+        return Raw{reinterpret_cast<const u32x4*>(p)[chunk]};
+    }
+    static __device__ __forceinline__ void unpack(const Raw& r, float (&v)[8])
+    {
+        for (int j = 0; j < 4; ++j) {
+            v[2 * j]     = __uint_as_float(r.w[j] << 16);
+            v[2 * j + 1] = __uint_as_float(r.w[j] & 0xFFFF0000u);
+        }
+    }
+    // round to nearest even (v_cvt_pk_bf16_f32)
+    static __device__ __forceinline__ uint32_t pack2(float lo, float hi)
+    {
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo, hi}, bf16x2));
+    }
+    static __device__ __forceinline__ void store(void* p, size_t chunk, const float (&v)[8])
+    {
+        reinterpret_cast<u32x4*>(p)[chunk] =
+            u32x4{pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7])};
+    }
+    static __device__ __forceinline__ float load1(const void* p, size_t i)
+    {
+        return __uint_as_float((uint32_t) reinterpret_cast<const uint16_t*>(p)[i] << 16);
+    }
+    static __device__ __forceinline__ void store1(void* p, size_t i, float v)
+    {
+        reinterpret_cast<uint16_t*>(p)[i] = (uint16_t)(pack2(v, 0.0f) & 0xFFFFu);
+    }
+};
+
+// ---------------------------------------------------------------------------
+// The four element-wise operations.  Each has
+//   In      -- the raw registers of one chunk of every input stream
+//   load    -- fill In for chunk c
+//   run     -- compute and store chunk c
+//   scalar  -- the same for the single element i (tail), returning the mask bit
+// ---------------------------------------------------------------------------
+
+template <int KIND, int DT>
+struct FwdOp {                       // y = f(x), s = [x < T]
+    using S = Storage<DT>;
+    const void* x; void* y; uint8_t* mask;
+    struct In { typename S::Raw x; };
+    __device__ __forceinline__ void load(In& in, size_t c) const { in.x = S::load(x, c); }
+    __device__ __forceinline__ void run(const In& in, size_t c) const
+    {
+        float v[8]; S::unpack(in.x, v);
+        uint32_t m = 0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            m |= (uint32_t)(v[j] < KindConst<KIND>::T) << j;
+            v[j] = act<KIND, S::kPrec>(v[j]);
+        }
+        S::store(y, c, v);
+        mask[c] = (uint8_t)m;
+    }
+    __device__ __forceinline__ bool scalar(size_t i, bool) const
+    {
+        float v = S::load1(x, i);
+        S::store1(y, i, act<KIND, S::kPrec>(v));
+        return v < KindConst<KIND>::T;
+    }
+    static constexpr bool kWritesMask = true;
+};
+
+template <int KIND, int DT>
+struct BwdOp {                       // grad_x = grad_y * q(y, s)
+    using S = Storage<DT>;
+    const void* y; const uint8_t* mask; const void* gy; void* gx;
+    struct In { typename S::Raw y, g; uint32_t m; };
+    __device__ __forceinline__ void load(In& in, size_t c) const
+    {
+        in.y = S::load(y, c); in.g = S::load(gy, c); in.m = mask[c];
+    }
+    __device__ __forceinline__ void run(const In& in, size_t c) const
+    {
+        float a[8], g[8]; S::unpack(in.y, a); S::unpack(in.g, g);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) g[j] *= q_approx<KIND>(a[j], (in.m >> j) & 1u);
+        S::store(gx, c, g);
+    }
+    __device__ __forceinline__ bool scalar(size_t i, bool bit) const
+    {
+        S::store1(gx, i, S::load1(gy, i) * q_approx<KIND>(S::load1(y, i), bit));
+        return bit;
+    }
+    static constexpr bool kWritesMask = false;
+};
+
+template <int KIND, int DT>
+struct GluFwdOp {                    // act = f(gate), s = [gate < T], h = f(gate) * up
+    using S = Storage<DT>;
+    const void* gate; const void* up; void* act_out; void* h; uint8_t* mask;
+    struct In { typename S::Raw g, u; };
+    __device__ __forceinline__ void load(In& in, size_t c) const
+    {
+        in.g = S::load(gate, c); in.u = S::load(up, c);
+    }
+    __device__ __forceinline__ void run(const In& in, size_t c) const
+    {
+        float v[8], u[8]; S::unpack(in.g, v); S::unpack(in.u, u);
+        uint32_t m = 0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            m |= (uint32_t)(v[j] < KindConst<KIND>::T) << j;
+            act_times<KIND, S::kPrec>(v[j], u[j], v[j], u[j]);
+        }
+        S::store(act_out, c, v);
+        S::store(h, c, u);
+        mask[c] = (uint8_t)m;
+    }
+    __device__ __forceinline__ bool scalar(size_t i, bool) const
+    {
+        float v = S::load1(gate, i), u = S::load1(up, i), a, p;
+        act_times<KIND, S::kPrec>(v, u, a, p);
+        S::store1(act_out, i, a);
+        S::store1(h, i, p);
+        return v < KindConst<KIND>::T;
+    }
+    static constexpr bool kWritesMask = true;
+};
+
+template <int KIND, int DT>
+struct GluBwdOp {                    // grad_up = grad_h * act ; grad_gate = grad_h * up * q(act, s)
+    using S = Storage<DT>;
+    const void* act_in; const void* up; const uint8_t* mask; const void* gh; void* ggate; void* gup;
+    struct In { typename S::Raw a, u, g; uint32_t m; };
+    __device__ __forceinline__ void load(In& in, size_t c) const
+    {
+        in.a = S::load(act_in, c); in.u = S::load(up, c); in.g = S::load(gh, c); in.m = mask[c];
+    }
+    __device__ __forceinline__ void run(const In& in, size_t c) const
+    {
+        float a[8], u[8], g[8]; S::unpack(in.a, a); S::unpack(in.u, u); S::unpack(in.g, g);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            float q = q_approx<KIND>(a[j], (in.m >> j) & 1u);
+            a[j] = g[j] * a[j];                  // grad_up
+            u[j] = product3<S::kPrec>(g[j], u[j], q);   // grad_gate
+        }
+        S::store(gup, c, a);
+        S::store(ggate, c, u);
+    }
+    __device__ __forceinline__ bool scalar(size_t i, bool bit) const
+    {
+        float a = S::load1(act_in, i), u = S::load1(up, i), g = S::load1(gh, i);
+        S::store1(gup, i, g * a);
+        S::store1(ggate, i, product3<S::kPrec>(g, u, q_approx<KIND>(a, bit)));
+        return bit;
+    }
+    static constexpr bool kWritesMask = false;
+};
+
+// ---------------------------------------------------------------------------
+// Skeleton
+// ---------------------------------------------------------------------------
+
+template <class Op>
+__global__ __launch_bounds__(kThreads) void stream_kernel(const Op op, const size_t n)
+{
+    const size_t chunks = n / 8;
+    const size_t stride = (size_t)gridDim.x * kThreads;
+    size_t c = (size_t)blockIdx.x * kThreads + threadIdx.x;
+
+    for (; c + (kUnroll - 1) * stride < chunks; c += kUnroll * stride) {
+        typename Op::In in[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) op.load(in[u], c + u * stride);
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) op.run(in[u], c + u * stride);
+    }
+    for (; c < chunks; c += stride) {
+        typename Op::In in;
+        op.load(in, c);
+        op.run(in, c);
+    }
+
+    // Tail: elements [8 chunks, n) and, in the forward kernels, the rest of the
+    // last 64-bit mask word.
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        const size_t first = chunks * 8;
+        if (first < n) {
+            const uint8_t* mask_in = nullptr;
+            if constexpr (!Op::kWritesMask) mask_in = op.mask;
+            uint32_t m = 0;
+            for (size_t i = first; i < n; ++i) {
+                bool bit = false;
+                if constexpr (!Op::kWritesMask) bit = (mask_in[chunks] >> (i - first)) & 1u;
+                m |= (uint32_t)op.scalar(i, bit) << (i - first);
+            }
+            if constexpr (Op::kWritesMask) op.mask[chunks] = (uint8_t)m;
+        }
+        if constexpr (Op::kWritesMask) {
+            const size_t used  = (n + 7) / 8;
+            const size_t total = 8 * ((n + 63) / 64);
+            for (size_t b = used; b < total; ++b) op.mask[b] = 0;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Host side
+// ---------------------------------------------------------------------------
+
+std::atomic<int> g_blocks_per_cu{kDefaultBlocksPerCu};
+std::atomic<int> g_cu_count[64];            // per device, 0 = not queried yet
+
+int cu_count()
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    int n = g_cu_count[dev].load(std::memory_order_relaxed);
+    if (n == 0) {
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        g_cu_count[dev].store(n, std::memory_order_relaxed);
+    }
+    return n;
+}
+
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+template <class Op>
+int launch(const Op& op, size_t n, hipStream_t stream)
+{
+    const size_t chunks = n / 8;
+    size_t blocks = (chunks + kThreads - 1) / kThreads;
+    const size_t cap = (size_t)cu_count() * (size_t)g_blocks_per_cu.load(std::memory_order_relaxed);
+    if (blocks > cap) blocks = cap;
+    if (blocks == 0) blocks = 1;
+    hipLaunchKernelGGL(stream_kernel<Op>, dim3((unsigned)blocks), dim3(kThreads), 0, stream, op, n);
+    return hipGetLastError() == hipSuccess ? INVACT_OK : INVACT_ERR_HIP;
+}
+
+// Runs fn<KIND, DT>() for the run-time (kind, dtype) pair.
+template <class F>
+int dispatch(int kind, int dtype, F&& fn)
+{
+#define INVACT_CASE(K, D) if (kind == K && dtype == D) return fn(std::integral_constant<int, K>{}, std::integral_constant<int, D>{});
+    INVACT_CASE(INVACT_GELU_TANH, INVACT_FP32) INVACT_CASE(INVACT_GELU_TANH, INVACT_BF16)
+    INVACT_CASE(INVACT_GELU_ERF,  INVACT_FP32) INVACT_CASE(INVACT_GELU_ERF,  INVACT_BF16)
+    INVACT_CASE(INVACT_SILU,      INVACT_FP32) INVACT_CASE(INVACT_SILU,      INVACT_BF16)
+#undef INVACT_CASE
+    return INVACT_ERR_KIND;
+}
+
+int check_common(int kind, int dtype, size_t n)
+{
+    if (kind != INVACT_GELU_TANH && kind != INVACT_GELU_ERF && kind != INVACT_SILU) return INVACT_ERR_KIND;
+    if (dtype != INVACT_FP32 && dtype != INVACT_BF16) return INVACT_ERR_DTYPE;
+    if (n > SIZE_MAX - 63) return INVACT_ERR_SIZE;
+    return INVACT_OK;
+}
+
+int check_ptrs(std::initializer_list<const void*> data, const void* mask)
+{
+    for (const void* p : data) if (p == nullptr) return INVACT_ERR_NULL;
+    if (mask == nullptr) return INVACT_ERR_NULL;
+    for (const void* p : data) if (!aligned(p, 16)) return INVACT_ERR_ALIGN;
+    if (!aligned(mask, 8)) return INVACT_ERR_ALIGN;
+    return INVACT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t invact_mask_bytes(size_t n) { return 8 * (n / 64 + (n % 64 != 0)); }
+
+const char* invact_strerror(int status)
+{
+    switch (status) {
+    case INVACT_OK:        return "success";
+    case INVACT_ERR_KIND:  return "unknown activation kind";
+    case INVACT_ERR_DTYPE: return "unknown dtype";
+    case INVACT_ERR_NULL:  return "null pointer argument";
+    case INVACT_ERR_ALIGN: return "pointer not aligned (16 bytes for tensors, 8 for the mask)";
+    case INVACT_ERR_SIZE:  return "element count too large";
+    case INVACT_ERR_HIP:   return "HIP runtime error at kernel launch";
+    }
+    return "unknown status";
+}
+
+int invact_set_blocks_per_cu(int blocks_per_cu)
+{
+    if (blocks_per_cu < 0 || blocks_per_cu > 64) return -1;
+    g_blocks_per_cu.store(blocks_per_cu == 0 ? kDefaultBlocksPerCu : blocks_per_cu, std::memory_order_relaxed);
+    return g_blocks_per_cu.load(std::memory_order_relaxed);
+}
+
+int invact_fwd(int kind, int dtype, const void* x, void* y, void* mask, size_t n, hipStream_t stream)
+{
+    if (int e = check_common(kind, dtype, n)) return e;
+    if (n == 0) return INVACT_OK;
+    if (int e = check_ptrs({x, y}, mask)) return e;
+    return dispatch(kind, dtype, [&](auto K, auto D) {
+        return launch(FwdOp<K.value, D.value>{x, y, static_cast<uint8_t*>(mask)}, n, stream);
+    });
+}
+
+int invact_bwd(int kind, int dtype, const void* y, const void* mask, const void* grad_y,
+               void* grad_x, size_t n, hipStream_t stream)
+{
+    if (int e = check_common(kind, dtype, n)) return e;
+    if (n == 0) return INVACT_OK;
+    if (int e = check_ptrs({y, grad_y, grad_x}, mask)) return e;
+    return dispatch(kind, dtype, [&](auto K, auto D) {
+        return launch(BwdOp<K.value, D.value>{y, static_cast<const uint8_t*>(mask), grad_y, grad_x}, n, stream);
+    });
+}
+
+int geglu_invact_fwd(int kind, int dtype, const void* gate, const void* up, void* act, void* h,
+                     void* mask, size_t n, hipStream_t stream)
+{
+    if (int e = check_common(kind, dtype, n)) return e;
+    if (n == 0) return INVACT_OK;
+    if (int e = check_ptrs({gate, up, act, h}, mask)) return e;
+    return dispatch(kind, dtype, [&](auto K, auto D) {
+        return launch(GluFwdOp<K.value, D.value>{gate, up, act, h, static_cast<uint8_t*>(mask)}, n, stream);
+    });
+}
+
+int geglu_invact_bwd(int kind, int dtype, const void* act, const void* up, const void* mask,
+                     const void* grad_h, void* grad_gate, void* grad_up, size_t n, hipStream_t stream)
+{
+    if (int e = check_common(kind, dtype, n)) return e;
+    if (n == 0) return INVACT_OK;
+    if (int e = check_ptrs({act, up, grad_h, grad_gate, grad_up}, mask)) return e;
+    return dispatch(kind, dtype, [&](auto K, auto D) {
+        return launch(GluBwdOp<K.value, D.value>{act, up, static_cast<const uint8_t*>(mask), grad_h,
+                                                 grad_gate, grad_up}, n, stream);
+    });
+}
+
+int swiglu_invact_fwd(int dtype, const void* gate, const void* up, void* act, void* h, void* mask,
+                      size_t n, hipStream_t stream)
+{
+    return geglu_invact_fwd(INVACT_SILU, dtype, gate, up, act, h, mask, n, stream);
+}
+
+int swiglu_invact_bwd(int dtype, const void* act, const void* up, const void* mask, const void* grad_h,
+                      void* grad_gate, void* grad_up, size_t n, hipStream_t stream)
+{
+    return geglu_invact_bwd(INVACT_SILU, dtype, act, up, mask, grad_h, grad_gate, grad_up, n, stream);
+}
+
+}  // extern "C"

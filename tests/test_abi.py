@@ -1,0 +1,90 @@
+"""The C ABI without a GPU: the library loads, exports every symbol the header
+declares, and rejects bad arguments before anything is launched."""
+import ctypes
+import os
+import re
+import subprocess
+
+import pytest
+
+from paper_2407_15545_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "invact.h")
+
+OK, ERR_KIND, ERR_DTYPE, ERR_NULL, ERR_ALIGN, ERR_SIZE, ERR_HIP = range(7)
+
+
+def declared_functions():
+    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+    return sorted(set(re.findall(r"\b((?:invact|swiglu_invact|geglu_invact)\w*)\s*\(", text)))
+
+
+def test_header_is_valid_c():
+    src = '#include "invact.h"\nint main(void) { return (int)invact_mask_bytes(3); }\n'
+    subprocess.run(["gcc", "-x", "c", "-fsyntax-only", "-D__HIP_PLATFORM_AMD__", "-I/opt/rocm/include",
+                    "-I" + os.path.join(ROOT, "include"), "-"], input=src.encode(), check=True)
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert {"invact_fwd", "invact_bwd", "swiglu_invact_fwd", "swiglu_invact_bwd", "geglu_invact_fwd",
+            "geglu_invact_bwd", "invact_mask_bytes", "invact_strerror"} <= set(names)
+    lib = B.lib()
+    for name in names:
+        assert hasattr(lib, name), name
+        assert name in B._PROTOTYPES, f"binding has no prototype for {name}"
+
+
+def test_mask_bytes():
+    for n, want in [(0, 0), (1, 8), (63, 8), (64, 8), (65, 16), (128, 16), (129, 24), (1 << 28, 1 << 25),
+                    (234881024, 29360128)]:
+        assert B.mask_bytes(n) == want
+    assert B.mask_bytes(2 ** 64 - 1) == 8 * ((2 ** 64 - 1 + 63) // 64)
+
+
+def test_strerror_texts_are_distinct():
+    texts = [B.strerror(i) for i in range(7)]
+    assert len(set(texts)) == 7 and texts[0] == "success"
+    assert B.strerror(99) == "unknown status"
+
+
+def test_argument_validation_happens_before_any_launch():
+    lib = B.lib()
+    a16, a8, odd = 0x1000, 0x1008, 0x1004          # never dereferenced: every call below is rejected
+    fwd, bwd = lib.invact_fwd, lib.invact_bwd
+    assert fwd(3, 0, a16, a16, a16, 8, None) == ERR_KIND
+    assert fwd(-1, 0, a16, a16, a16, 8, None) == ERR_KIND
+    assert fwd(0, 2, a16, a16, a16, 8, None) == ERR_DTYPE
+    assert fwd(0, 0, None, a16, a16, 8, None) == ERR_NULL
+    assert fwd(0, 0, a16, None, a16, 8, None) == ERR_NULL
+    assert fwd(0, 0, a16, a16, None, 8, None) == ERR_NULL
+    assert fwd(0, 0, a8, a16, a16, 8, None) == ERR_ALIGN
+    assert fwd(0, 1, a16, a8, a16, 8, None) == ERR_ALIGN
+    assert fwd(0, 1, a16, a16, odd, 8, None) == ERR_ALIGN
+    assert fwd(0, 0, a16, a16, a16, 2 ** 64 - 1, None) == ERR_SIZE
+    assert bwd(0, 0, a16, a16, None, a16, 8, None) == ERR_NULL
+    assert bwd(0, 0, a16, odd, a16, a16, 8, None) == ERR_ALIGN
+    assert bwd(2, 5, a16, a16, a16, a16, 8, None) == ERR_DTYPE
+    assert lib.geglu_invact_fwd(9, 1, a16, a16, a16, a16, a16, 8, None) == ERR_KIND
+    assert lib.geglu_invact_bwd(0, 1, a16, a16, a16, a16, a16, None, 8, None) == ERR_NULL
+    assert lib.swiglu_invact_fwd(1, a16, a16, a16, a8, a16, 8, None) == ERR_ALIGN
+    assert lib.swiglu_invact_bwd(7, a16, a16, a16, a16, a16, a16, 8, None) == ERR_DTYPE
+    # n == 0 is a successful no-op, whatever the pointers
+    assert fwd(0, 0, None, None, None, 0, None) == OK
+    assert bwd(2, 1, None, None, None, None, 0, None) == OK
+    assert lib.swiglu_invact_bwd(1, None, None, None, None, None, None, 0, None) == OK
+
+
+def test_blocks_per_cu_range():
+    try:
+        assert B.set_blocks_per_cu(4) == 4
+        assert B.set_blocks_per_cu(65) < 0 and B.set_blocks_per_cu(-1) < 0
+    finally:
+        assert B.set_blocks_per_cu(0) > 0
+
+
+def test_binding_raises_with_the_library_message():
+    with pytest.raises(B.InvactError) as e:
+        B._check(ERR_ALIGN)
+    assert "aligned" in str(e.value) and e.value.status == ERR_ALIGN

@@ -1,0 +1,325 @@
+"""GPU parity: libinvact (through its C ABI, via the ctypes binding) against the
+CPU oracle, element by element, on the same seeded inputs.
+
+Sizes here are ones the oracle finishes in seconds; they span many 8-element
+chunks, several workgroups and ragged tails.  Full-size workloads are in
+test_gpu_workloads.py.
+"""
+import os
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+import parity as PT
+from paper_2407_15545_amd import binding as B
+from paper_2407_15545_amd import synth
+
+pytestmark = pytest.mark.gpu
+REPORT_DIR = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+
+KINDS = ["gelu_tanh", "gelu_erf", "silu"]
+DTYPES = ["fp32", "bf16"]
+SIZES = [1, 7, 8, 63, 64, 65, 511, 513, 4096 + 8, (1 << 20) + 3]
+
+
+def say(*a):
+    """Name the case before the GPU step (stderr, flushed); keep a copy where GPU runs leave their files."""
+    print(*a, file=sys.stderr, flush=True)
+    if os.path.isdir(REPORT_DIR):
+        with open(os.path.join(REPORT_DIR, "parity_report.txt"), "a") as fh:
+            print(*a, file=fh)
+
+
+def draw(n, seed, dtype, std=2.0):
+    return synth.to_storage(synth.normal(n, seed, std), dtype)
+
+
+def mask_of(t):
+    return t.cpu().numpy()
+
+
+# ---------------------------------------------------------------- invact_fwd
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("kind", KINDS)
+def test_fwd_matches_oracle(kind, dtype):
+    for n in SIZES:
+        say(f"invact_fwd {kind} {dtype} n={n}")
+        xs = draw(n, n, dtype)
+        x64 = synth.storage_to_f64(xs, dtype)
+        ye, _, m_ref = O.invact_fwd(kind, dtype, x64)
+        y, m = B.invact_fwd(kind, PT.to_device(xs, dtype))
+        torch.cuda.synchronize()
+        assert m.numel() == O.mask_bytes(n)
+        assert np.array_equal(mask_of(m), m_ref), f"mask differs, n={n}"
+        err = PT.forward_errors(PT.to_f64(y), ye, dtype)
+        assert err.max() <= 1.0, (n, PT.worst(err, x64, ye, PT.to_f64(y)))
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("kind", KINDS)
+def test_fwd_every_bf16_input(kind, dtype):
+    """All 65 536 bfloat16 patterns as inputs (as binary32 values for the fp32 path)."""
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    xs = bits if dtype == "bf16" else synth.bf16_bits_to_f32(bits)
+    with np.errstate(invalid="ignore"):
+        x64 = synth.storage_to_f64(xs, dtype)
+    ye, _, m_ref = O.invact_fwd(kind, dtype, x64)
+    say(f"invact_fwd {kind} {dtype} all bf16 patterns")
+    y, m = B.invact_fwd(kind, PT.to_device(xs, dtype))
+    torch.cuda.synchronize()
+    assert np.array_equal(mask_of(m), m_ref)
+    err = PT.forward_errors(PT.to_f64(y), ye, dtype)
+    assert err.max() <= 1.0, PT.worst(err, x64, ye, PT.to_f64(y))
+    # signed zero of the far left tail and of -inf
+    got = PT.to_f64(y)
+    ninf = int(np.where(bits == 0xFF80)[0][0])
+    assert got[ninf] == 0 and np.signbit(got[ninf])
+    assert got[int(np.where(bits == 0x7F80)[0][0])] == np.inf
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_fwd_fp32_dense_ranges(kind):
+    """binary32 forward on dense sweeps of every binade that matters, incl. the left tail."""
+    rng = np.random.default_rng(11)
+    parts = [rng.uniform(-110, 0, 1 << 18), rng.uniform(0, 110, 1 << 16), rng.uniform(-14, -4, 1 << 18),
+             rng.uniform(-2, 2, 1 << 18), -np.exp2(rng.uniform(-140, 7, 1 << 16)), np.exp2(rng.uniform(-140, 127, 1 << 16))]
+    xs = np.concatenate(parts).astype(np.float32)
+    x64 = xs.astype(np.float64)
+    ye, _, m_ref = O.invact_fwd(kind, "fp32", x64)
+    say(f"invact_fwd {kind} fp32 dense ranges n={xs.size}")
+    y, m = B.invact_fwd(kind, PT.to_device(xs, "fp32"))
+    torch.cuda.synchronize()
+    assert np.array_equal(mask_of(m), m_ref)
+    err = PT.forward_errors(PT.to_f64(y), ye, "fp32")
+    assert err.max() <= 1.0, PT.worst(err, x64, ye, PT.to_f64(y))
+
+
+# ---------------------------------------------------------------- invact_bwd
+
+def bwd_case(kind, dtype, n, seed):
+    xs = draw(n, seed, dtype)
+    gs = draw(n, seed + 1, dtype, 1.0)
+    x64 = synth.storage_to_f64(xs, dtype)
+    g64 = synth.storage_to_f64(gs, dtype)
+    _, ys64, m_ref = O.invact_fwd(kind, dtype, x64)
+    return ys64, m_ref, gs, g64
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("kind", KINDS)
+def test_bwd_matches_oracle(kind, dtype):
+    for n in SIZES:
+        say(f"invact_bwd {kind} {dtype} n={n}")
+        ys64, m_ref, gs, g64 = bwd_case(kind, dtype, n, 100 + n)
+        ref = O.invact_bwd(kind, ys64, m_ref, g64)
+        y_dev = PT.to_device(synth.f64_to_storage_exact(ys64, dtype), dtype)
+        gx = B.invact_bwd(kind, y_dev, torch.from_numpy(m_ref).cuda(), PT.to_device(gs, dtype))
+        torch.cuda.synchronize()
+        err = PT.backward_errors(PT.to_f64(gx), ref, g64, dtype)
+        assert err.max() <= 1.0, (n, PT.worst(err, ys64, g64, ref, PT.to_f64(gx)))
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_bwd_every_bf16_y_and_both_mask_bits(kind):
+    """All 131 072 (y, s) pairs with y a bfloat16 pattern, grad_y = 1.
+
+    Pairs the forward can produce, and their neighbourhood (y within [-1, 1] on
+    the left branch, any y on the right branch), must match the oracle.  For
+    left-branch pairs far outside the range of f the binary32 evaluation
+    overflows where the double one does not; there only NaN-ness and the
+    absence of a fault are checked."""
+    bits = np.tile(np.arange(65536, dtype=np.uint32).astype(np.uint16), 2)
+    s = np.repeat(np.array([0, 1], np.uint8), 65536)
+    with np.errstate(invalid="ignore"):
+        y64 = synth.storage_to_f64(bits, "bf16")
+    m = O.pack(s)
+    g = np.ones(bits.size)
+    ref = O.invact_bwd(kind, y64, m, g)
+    say(f"invact_bwd {kind} bf16 all (y, s) pairs")
+    gx = B.invact_bwd(kind, PT.to_device(bits, "bf16"), torch.from_numpy(m).cuda(),
+                      PT.to_device(synth.to_storage(g.astype(np.float32), "bf16"), "bf16"))
+    torch.cuda.synchronize()
+    got = PT.to_f64(gx)
+    with np.errstate(invalid="ignore"):
+        strict = (s == 0) | (np.abs(y64) <= 1.0) | np.isnan(y64)
+    err = PT.backward_errors(got[strict], ref[strict], g[strict], "bf16")
+    assert err.max() <= 1.0, PT.worst(err, y64[strict], s[strict].astype(float), ref[strict], got[strict])
+    assert np.all(np.isnan(got[np.isnan(y64)]))
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_bwd_fp32_dense_in_y(kind):
+    """binary32 backward on y dense over the range of f on both branches (valid pairs only)."""
+    rng = np.random.default_rng(17)
+    fT = O.fT(kind, f32=True)
+    yl = np.concatenate([rng.uniform(fT, 0, 1 << 18), fT + np.exp2(rng.uniform(-30, -3, 1 << 16)),
+                         -np.exp2(rng.uniform(-60, -3, 1 << 16))])
+    yr = np.concatenate([rng.uniform(fT, 1, 1 << 18), rng.uniform(1, 40, 1 << 17),
+                         fT + np.exp2(rng.uniform(-30, -3, 1 << 16)), np.exp2(rng.uniform(-40, 100, 1 << 14)),
+                         [fT, fT - 1e-4, np.inf, 64.0, 65.0, 1e30]])
+    y = np.concatenate([yl, yr]).astype(np.float32)
+    y = np.maximum(y, np.float32(fT) - np.float32(2e-4))
+    s = np.concatenate([np.ones(yl.size, np.uint8), np.zeros(yr.size, np.uint8)])
+    g = rng.standard_normal(y.size).astype(np.float32)
+    m = O.pack(s)
+    ref = O.invact_bwd(kind, y.astype(np.float64), m, g.astype(np.float64))
+    say(f"invact_bwd {kind} fp32 dense y n={y.size}")
+    gx = B.invact_bwd(kind, PT.to_device(y, "fp32"), torch.from_numpy(m).cuda(), PT.to_device(g, "fp32"))
+    torch.cuda.synchronize()
+    got = PT.to_f64(gx)
+    err = PT.backward_errors(got, ref, g.astype(np.float64), "fp32")
+    assert err.max() <= 1.0, PT.worst(err, y.astype(np.float64), s.astype(float), ref, got)
+    # reported: the plain result-relative figure the tolerance rule replaces
+    lit = PT.literal_ulps(got, ref, "fp32")
+    fin = np.isfinite(lit)
+    absq = np.abs(got - ref)[fin] / np.abs(g)[fin]
+    small = np.abs(ref[fin] / g[fin]) < 0.5
+    say(f"  {kind}: max |gpu-ref|/|g| = {absq.max():.3g} (where |q| < 0.5: {absq[small].max():.3g}), "
+        f"literal max ulp = {lit[fin].max():.3g}, share over 2 ulp = {(lit[fin] > 2).mean():.3g}")
+
+
+# ---------------------------------------------------------------- gated block
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("kind", KINDS)
+def test_gated_fwd_bwd_match_oracle(kind, dtype):
+    for n in SIZES:
+        say(f"geglu fwd/bwd {kind} {dtype} n={n}")
+        gate_s, up_s, gh_s = draw(n, 200 + n, dtype, 1.5), draw(n, 201 + n, dtype, 1.0), draw(n, 202 + n, dtype, 0.01)
+        gate, up, gh = (synth.storage_to_f64(a, dtype) for a in (gate_s, up_s, gh_s))
+        ae, as_, he, m_ref = O.glu_fwd(kind, dtype, gate, up)
+        act, h, m = B.geglu_invact_fwd(kind, PT.to_device(gate_s, dtype), PT.to_device(up_s, dtype))
+        torch.cuda.synchronize()
+        assert np.array_equal(mask_of(m), m_ref)
+        e1 = PT.forward_errors(PT.to_f64(act), ae, dtype)
+        e2 = PT.forward_errors(PT.to_f64(h), he, dtype)
+        assert e1.max() <= 1.0, (n, PT.worst(e1, gate, ae, PT.to_f64(act)))
+        assert e2.max() <= 1.0, (n, PT.worst(e2, gate, up, he, PT.to_f64(h)))
+        # backward from what the ORACLE's forward saved
+        gg_ref, gu_ref = O.glu_bwd(kind, as_, up, m_ref, gh)
+        act_dev = PT.to_device(synth.f64_to_storage_exact(as_, dtype), dtype)
+        gg, gu = B.geglu_invact_bwd(kind, act_dev, PT.to_device(up_s, dtype), torch.from_numpy(m_ref).cuda(),
+                                    PT.to_device(gh_s, dtype))
+        torch.cuda.synchronize()
+        e3 = PT.forward_errors(PT.to_f64(gu), gu_ref, dtype)          # plain product: 2 ulp literally
+        e4 = PT.backward_errors(PT.to_f64(gg), gg_ref, gh * up, dtype)
+        assert e3.max() <= 1.0, (n, PT.worst(e3, gh, as_, gu_ref, PT.to_f64(gu)))
+        assert e4.max() <= 1.0, (n, PT.worst(e4, as_, gh * up, gg_ref, PT.to_f64(gg)))
+
+
+def test_swiglu_entry_points_equal_geglu_with_silu():
+    n = 70001
+    gate_s, up_s, gh_s = draw(n, 5, "bf16"), draw(n, 6, "bf16", 1.0), draw(n, 7, "bf16", 0.01)
+    gate, up, gh = (PT.to_device(a, "bf16") for a in (gate_s, up_s, gh_s))
+    say("swiglu_invact_fwd/bwd vs geglu(silu)")
+    a1, h1, m1 = B.swiglu_invact_fwd(gate, up)
+    a2, h2, m2 = B.geglu_invact_fwd("silu", gate, up)
+    g1 = B.swiglu_invact_bwd(a1, up, m1, gh)
+    g2 = B.geglu_invact_bwd("silu", a2, up, m2, gh)
+    torch.cuda.synchronize()
+    for p, q in ((a1, a2), (h1, h2), (m1, m2), (g1[0], g2[0]), (g1[1], g2[1])):
+        assert torch.equal(p.view(torch.uint8) if p.dtype != torch.uint8 else p,
+                           q.view(torch.uint8) if q.dtype != torch.uint8 else q)
+
+
+# ---------------------------------------------------------------- contract details
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_in_place_and_canaries(dtype):
+    """Element-wise aliasing is allowed, and nothing is written past the outputs."""
+    kind, n = "silu", 100003
+    pad = 64
+    xs = draw(n, 31, dtype)
+    gs = draw(n, 32, dtype, 1.0)
+    x = PT.to_device(xs, dtype)
+    td = PT.TORCH_DTYPE[dtype]
+    say(f"in-place / canaries {dtype}")
+    # reference results out of place
+    y_ref, m_ref = B.invact_fwd(kind, x)
+    gx_ref = B.invact_bwd(kind, y_ref, m_ref, PT.to_device(gs, dtype))
+    # outputs carved out of larger buffers whose surroundings hold a canary
+    nb = B.mask_bytes(n)
+    ybuf = torch.full((n + 2 * pad,), 7.0, dtype=td, device="cuda")
+    mbuf = torch.full((nb + 2 * pad,), 0xAB, dtype=torch.uint8, device="cuda")
+    yv, mv = ybuf[pad:pad + n], mbuf[pad:pad + nb]
+    yv.copy_(x)
+    B.invact_fwd(kind, yv, y=yv, mask=mv)                         # y == x
+    torch.cuda.synchronize()
+    assert torch.equal(yv.view(torch.uint8), y_ref.view(torch.uint8)) and torch.equal(mv, m_ref)
+    assert bool((ybuf[:pad] == 7.0).all()) and bool((ybuf[pad + n:] == 7.0).all())
+    assert bool((mbuf[:pad] == 0xAB).all()) and bool((mbuf[pad + nb:] == 0xAB).all())
+    gbuf = torch.full((n + 2 * pad,), 7.0, dtype=td, device="cuda")
+    gv = gbuf[pad:pad + n]
+    gv.copy_(PT.to_device(gs, dtype))
+    B.invact_bwd(kind, y_ref, m_ref, gv, grad_x=gv)               # grad_x == grad_y
+    torch.cuda.synchronize()
+    assert torch.equal(gv.view(torch.uint8), gx_ref.view(torch.uint8))
+    assert bool((gbuf[:pad] == 7.0).all()) and bool((gbuf[pad + n:] == 7.0).all())
+    # gated: grad_up == grad_h
+    up = PT.to_device(draw(n, 33, dtype, 1.0), dtype)
+    gg_ref, gu_ref = B.geglu_invact_bwd(kind, y_ref, up, m_ref, PT.to_device(gs, dtype))
+    gv.copy_(PT.to_device(gs, dtype))
+    gg, gu = B.geglu_invact_bwd(kind, y_ref, up, m_ref, gv, grad_up=gv)
+    torch.cuda.synchronize()
+    assert torch.equal(gg.view(torch.uint8), gg_ref.view(torch.uint8))
+    assert torch.equal(gu.view(torch.uint8), gu_ref.view(torch.uint8))
+
+
+def test_mask_padding_is_rewritten_as_zero():
+    for n in (1, 9, 65, 127, 129, 1000):
+        m = torch.full((B.mask_bytes(n),), 0xFF, dtype=torch.uint8, device="cuda")
+        x = torch.full((n,), -5.0, dtype=torch.bfloat16, device="cuda")      # every bit set
+        say(f"mask padding n={n}")
+        B.invact_fwd("silu", x, mask=m)
+        torch.cuda.synchronize()
+        assert np.array_equal(m.cpu().numpy(), O.pack(np.ones(n, np.uint8)))
+
+
+def test_other_stream_and_grid_shapes_give_identical_bits():
+    n = (1 << 22) + 13
+    xs = draw(n, 41, "bf16")
+    x = PT.to_device(xs, "bf16")
+    say("streams / grid shapes")
+    y0, m0 = B.invact_fwd("gelu_erf", x)
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        y1, m1 = B.invact_fwd("gelu_erf", x)
+    s.synchronize()
+    assert torch.equal(y0.view(torch.int16), y1.view(torch.int16)) and torch.equal(m0, m1)
+    try:
+        for bpc in (1, 3, 16, 64):
+            assert B.set_blocks_per_cu(bpc) == bpc
+            y2, m2 = B.invact_fwd("gelu_erf", x)
+            torch.cuda.synchronize()
+            assert torch.equal(y0.view(torch.int16), y2.view(torch.int16)) and torch.equal(m0, m2), bpc
+    finally:
+        B.set_blocks_per_cu(0)
+
+
+def test_nan_and_infinities_flow_through():
+    special = [float("nan"), float("inf"), float("-inf"), 0.0, -0.0, 1.0, -1.0, -3.0] * 3
+    for dtype in DTYPES:
+        td = PT.TORCH_DTYPE[dtype]
+        x = torch.tensor(special, dtype=td, device="cuda")
+        x64 = np.array(special, dtype=np.float64)
+        g = torch.ones_like(x)
+        for kind in KINDS:
+            say(f"specials {kind} {dtype}")
+            ye, ys, mr = O.invact_fwd(kind, dtype, x64)
+            y, m = B.invact_fwd(kind, x)
+            # backward from what the oracle's forward saved
+            y_saved = PT.to_device(synth.f64_to_storage_exact(ys, dtype), dtype)
+            gx = B.invact_bwd(kind, y_saved, torch.from_numpy(mr).cuda(), g)
+            torch.cuda.synchronize()
+            yv, gv = PT.to_f64(y), PT.to_f64(gx)
+            assert np.array_equal(m.cpu().numpy(), mr)
+            assert PT.forward_errors(yv, ye, dtype).max() <= 1.0
+            assert np.isnan(yv[0]) and yv[1] == np.inf and yv[2] == 0 and np.signbit(yv[2])
+            assert np.isnan(gv[0]) and gv[1] == 1.0
+            ref = O.invact_bwd(kind, ys, mr, np.ones(x.numel()))
+            assert PT.backward_errors(gv, ref, np.ones(x.numel()), dtype).max() <= 1.0
