@@ -48,7 +48,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--cpu-elems", type=int, default=1 << 25, help="elements of the CPU-baseline slice (0 = skip)")
+    ap.add_argument("--cpu-elems", type=int, default=1 << 28, help="elements of the CPU-baseline slice (0 = skip)")
     ap.add_argument("--blocks-per-cu", type=int, default=0)
     ap.add_argument("--elements", type=int, default=0, help="override the element count (debugging only)")
     args = ap.parse_args()

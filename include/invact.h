@@ -112,10 +112,11 @@ int swiglu_invact_bwd(int dtype, const void* act, const void* up,
                       void* grad_gate, void* grad_up, size_t n, hipStream_t stream);
 
 /*
- * Launch tuning (process-wide, for benchmarking): number of 256-thread
- * workgroups per compute unit the grid-stride kernels are launched with.
- * 0 restores the built-in default.  Returns the value now in force, or a
- * negative number if `blocks_per_cu` is out of range (0..64).
+ * Launch tuning (process-wide, for benchmarking).  By default every 256-thread
+ * workgroup handles one tile and retires.  blocks_per_cu in 1..64 switches to
+ * a persistent grid of that many workgroups per compute unit striding over
+ * the tensor; 0 restores the default.  Results are bit-identical either way.
+ * Returns blocks_per_cu, or a negative number if it is out of range.
  */
 int invact_set_blocks_per_cu(int blocks_per_cu);
 

@@ -21,12 +21,12 @@ def up_to_date():
     return os.path.exists(LIB) and all(os.path.getmtime(LIB) >= os.path.getmtime(d) for d in DEPS)
 
 
-def build(force=True, verbose=False, extra=()):
+def build(force=True, verbose=False, extra=(), out=LIB):
     """Compile the library.  Returns its path."""
-    if not force and up_to_date():
+    if not force and out == LIB and up_to_date():
         return LIB
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, *extra, "-o", LIB, SRC]
+    cmd = [hipcc, *HIPCC_FLAGS, *extra, "-o", out, SRC]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)

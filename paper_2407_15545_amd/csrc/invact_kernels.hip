@@ -25,9 +25,29 @@ namespace {
 
 using namespace invact_dev;
 
-constexpr int kThreads = 256;
-constexpr int kUnroll  = 2;
-constexpr int kDefaultBlocksPerCu = 8;
+#ifndef INVACT_UNROLL
+#define INVACT_UNROLL 2
+#endif
+#ifndef INVACT_NT
+#define INVACT_NT 1
+#endif
+#ifndef INVACT_DEFAULT_BLOCKS_PER_CU
+#define INVACT_DEFAULT_BLOCKS_PER_CU 0
+#endif
+
+constexpr int  kThreads = 256;
+constexpr int  kUnroll  = INVACT_UNROLL;          // chunks in flight per lane
+constexpr bool kNonTemporal = INVACT_NT != 0;     // every byte is touched once: keep it out of the caches
+constexpr int  kDefaultBlocksPerCu = INVACT_DEFAULT_BLOCKS_PER_CU;   // 0: one tile per workgroup
+
+template <class T> __device__ __forceinline__ T ld(const T* p)
+{
+    if constexpr (kNonTemporal) return __builtin_nontemporal_load(p); else return *p;
+}
+template <class T> __device__ __forceinline__ void st(T* p, T v)
+{
+    if constexpr (kNonTemporal) __builtin_nontemporal_store(v, p); else *p = v;
+}
 
 typedef float    f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -46,7 +66,7 @@ template <> struct Storage<INVACT_FP32> {
     static __device__ __forceinline__ Raw load(const void* p, size_t chunk)
     {
         const f32x4* q = reinterpret_cast<const f32x4*>(p) + 2 * chunk;
-        return Raw{q[0], q[1]};
+        return Raw{ld(q), ld(q + 1)};
     }
     static __device__ __forceinline__ void unpack(const Raw& r, float (&v)[8])
     {
@@ -55,8 +75,8 @@ template <> struct Storage<INVACT_FP32> {
     static __device__ __forceinline__ void store(void* p, size_t chunk, const float (&v)[8])
     {
         f32x4* q = reinterpret_cast<f32x4*>(p) + 2 * chunk;
-        q[0] = f32x4{v[0], v[1], v[2], v[3]};
-        q[1] = f32x4{v[4], v[5], v[6], v[7]};
+        st(q, f32x4{v[0], v[1], v[2], v[3]});
+        st(q + 1, f32x4{v[4], v[5], v[6], v[7]});
     }
     static __device__ __forceinline__ float load1(const void* p, size_t i) { return reinterpret_cast<const float*>(p)[i]; }
     static __device__ __forceinline__ void store1(void* p, size_t i, float v) { reinterpret_cast<float*>(p)[i] = v; }
@@ -67,7 +87,7 @@ template <> struct Storage<INVACT_BF16> {
     static constexpr int kPrec = FAST;
     static __device__ __forceinline__ Raw load(const void* p, size_t chunk)
     {
-        return Raw{reinterpret_cast<const u32x4*>(p)[chunk]};
+        return Raw{ld(reinterpret_cast<const u32x4*>(p) + chunk)};
     }
     static __device__ __forceinline__ void unpack(const Raw& r, float (&v)[8])
     {
@@ -83,8 +103,8 @@ template <> struct Storage<INVACT_BF16> {
     }
     static __device__ __forceinline__ void store(void* p, size_t chunk, const float (&v)[8])
     {
-        reinterpret_cast<u32x4*>(p)[chunk] =
-            u32x4{pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7])};
+        st(reinterpret_cast<u32x4*>(p) + chunk,
+           u32x4{pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7])});
     }
     static __device__ __forceinline__ float load1(const void* p, size_t i)
     {
@@ -120,7 +140,7 @@ struct FwdOp {                       // y = f(x), s = [x < T]
             v[j] = act<KIND, S::kPrec>(v[j]);
         }
         S::store(y, c, v);
-        mask[c] = (uint8_t)m;
+        st(mask + c, (uint8_t)m);
     }
     __device__ __forceinline__ bool scalar(size_t i, bool) const
     {
@@ -138,7 +158,7 @@ struct BwdOp {                       // grad_x = grad_y * q(y, s)
     struct In { typename S::Raw y, g; uint32_t m; };
     __device__ __forceinline__ void load(In& in, size_t c) const
     {
-        in.y = S::load(y, c); in.g = S::load(gy, c); in.m = mask[c];
+        in.y = S::load(y, c); in.g = S::load(gy, c); in.m = ld(mask + c);
     }
     __device__ __forceinline__ void run(const In& in, size_t c) const
     {
@@ -175,7 +195,7 @@ struct GluFwdOp {                    // act = f(gate), s = [gate < T], h = f(gat
         }
         S::store(act_out, c, v);
         S::store(h, c, u);
-        mask[c] = (uint8_t)m;
+        st(mask + c, (uint8_t)m);
     }
     __device__ __forceinline__ bool scalar(size_t i, bool) const
     {
@@ -195,7 +215,7 @@ struct GluBwdOp {                    // grad_up = grad_h * act ; grad_gate = gra
     struct In { typename S::Raw a, u, g; uint32_t m; };
     __device__ __forceinline__ void load(In& in, size_t c) const
     {
-        in.a = S::load(act_in, c); in.u = S::load(up, c); in.g = S::load(gh, c); in.m = mask[c];
+        in.a = S::load(act_in, c); in.u = S::load(up, c); in.g = S::load(gh, c); in.m = ld(mask + c);
     }
     __device__ __forceinline__ void run(const In& in, size_t c) const
     {
@@ -223,24 +243,47 @@ struct GluBwdOp {                    // grad_up = grad_h * act ; grad_gate = gra
 // Skeleton
 // ---------------------------------------------------------------------------
 
-template <class Op>
+// PERSISTENT: the grid strides over the chunks (a fixed number of workgroups
+// per compute unit).  Otherwise every workgroup handles one tile of
+// kUnroll * kThreads chunks and retires, and the dispatcher balances the load.
+template <class Op, bool PERSISTENT>
 __global__ __launch_bounds__(kThreads) void stream_kernel(const Op op, const size_t n)
 {
     const size_t chunks = n / 8;
-    const size_t stride = (size_t)gridDim.x * kThreads;
-    size_t c = (size_t)blockIdx.x * kThreads + threadIdx.x;
 
-    for (; c + (kUnroll - 1) * stride < chunks; c += kUnroll * stride) {
-        typename Op::In in[kUnroll];
+    if constexpr (PERSISTENT) {
+        const size_t stride = (size_t)gridDim.x * kThreads;
+        size_t c = (size_t)blockIdx.x * kThreads + threadIdx.x;
+        for (; c + (kUnroll - 1) * stride < chunks; c += kUnroll * stride) {
+            typename Op::In in[kUnroll];
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) op.load(in[u], c + u * stride);
+            for (int u = 0; u < kUnroll; ++u) op.load(in[u], c + u * stride);
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) op.run(in[u], c + u * stride);
-    }
-    for (; c < chunks; c += stride) {
-        typename Op::In in;
-        op.load(in, c);
-        op.run(in, c);
+            for (int u = 0; u < kUnroll; ++u) op.run(in[u], c + u * stride);
+        }
+        for (; c < chunks; c += stride) {
+            typename Op::In in;
+            op.load(in, c);
+            op.run(in, c);
+        }
+    } else {
+        const size_t c = (size_t)blockIdx.x * (kThreads * kUnroll) + threadIdx.x;
+        if (c + (kUnroll - 1) * kThreads < chunks) {
+            typename Op::In in[kUnroll];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) op.load(in[u], c + u * kThreads);
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) op.run(in[u], c + u * kThreads);
+        } else {
+            for (int u = 0; u < kUnroll; ++u) {
+                const size_t cu = c + u * kThreads;
+                if (cu < chunks) {
+                    typename Op::In in;
+                    op.load(in, cu);
+                    op.run(in, cu);
+                }
+            }
+        }
     }
 
     // Tail: elements [8 chunks, n) and, in the forward kernels, the rest of the
@@ -291,11 +334,19 @@ template <class Op>
 int launch(const Op& op, size_t n, hipStream_t stream)
 {
     const size_t chunks = n / 8;
-    size_t blocks = (chunks + kThreads - 1) / kThreads;
-    const size_t cap = (size_t)cu_count() * (size_t)g_blocks_per_cu.load(std::memory_order_relaxed);
-    if (blocks > cap) blocks = cap;
-    if (blocks == 0) blocks = 1;
-    hipLaunchKernelGGL(stream_kernel<Op>, dim3((unsigned)blocks), dim3(kThreads), 0, stream, op, n);
+    const int per_cu = g_blocks_per_cu.load(std::memory_order_relaxed);
+    if (per_cu == 0) {
+        size_t blocks = (chunks + kThreads * kUnroll - 1) / (kThreads * kUnroll);
+        if (blocks == 0) blocks = 1;                          // the tail still needs a thread
+        if (blocks > 0x7FFFFFFFu) return INVACT_ERR_SIZE;
+        hipLaunchKernelGGL((stream_kernel<Op, false>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, op, n);
+    } else {
+        size_t blocks = (chunks + kThreads - 1) / kThreads;
+        const size_t cap = (size_t)cu_count() * (size_t)per_cu;
+        if (blocks > cap) blocks = cap;
+        if (blocks == 0) blocks = 1;
+        hipLaunchKernelGGL((stream_kernel<Op, true>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, op, n);
+    }
     return hipGetLastError() == hipSuccess ? INVACT_OK : INVACT_ERR_HIP;
 }
 
@@ -352,7 +403,7 @@ int invact_set_blocks_per_cu(int blocks_per_cu)
 {
     if (blocks_per_cu < 0 || blocks_per_cu > 64) return -1;
     g_blocks_per_cu.store(blocks_per_cu == 0 ? kDefaultBlocksPerCu : blocks_per_cu, std::memory_order_relaxed);
-    return g_blocks_per_cu.load(std::memory_order_relaxed);
+    return blocks_per_cu;
 }
 
 int invact_fwd(int kind, int dtype, const void* x, void* y, void* mask, size_t n, hipStream_t stream)

@@ -81,7 +81,7 @@ def test_blocks_per_cu_range():
         assert B.set_blocks_per_cu(4) == 4
         assert B.set_blocks_per_cu(65) < 0 and B.set_blocks_per_cu(-1) < 0
     finally:
-        assert B.set_blocks_per_cu(0) > 0
+        assert B.set_blocks_per_cu(0) == 0
 
 
 def test_binding_raises_with_the_library_message():
