@@ -26,6 +26,10 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 HBM_PEAK_GBS = 8000.0
 WORKLOAD = "swiglu_bf16_4x4096x14336"
 BYTES_FWD, BYTES_BWD = 8.125, 10.125          # per element, bf16
+# HBM bytes one swiglu_invact_bwd launch moves on the full workload, from rocprofv3's
+# FETCH_SIZE and WRITE_SIZE counters scaled by their readings for a plain copy
+# (profiles/swiglu_bf16_4x4096x14336.md): 1442.2 MB read + 939.5 MB written.
+TRAFFIC_BWD_FULL = 2381.7e6
 
 
 def cpu_baseline(w, n_slice):
@@ -51,6 +55,10 @@ def main():
     ap.add_argument("--cpu-elems", type=int, default=1 << 28, help="elements of the CPU-baseline slice (0 = skip)")
     ap.add_argument("--blocks-per-cu", type=int, default=0)
     ap.add_argument("--elements", type=int, default=0, help="override the element count (debugging only)")
+    ap.add_argument("--calibration-copies", type=int, default=0,
+                    help="after the timed steps, run this many plain device copies of one tensor (reads and "
+                         "writes 2 bytes per element each): the known traffic that rocprofv3's FETCH_SIZE / "
+                         "WRITE_SIZE readings are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: the path is element-wise and needs no exchange between GPUs, "
@@ -94,6 +102,10 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
+    for _ in range(args.calibration_copies):
+        act.copy_(gate)
+    torch.cuda.synchronize()
+
     ms_step = wall * 1e3 / args.steps
     fwd_ms = sum(e[0].elapsed_time(e[1]) for e in events) / args.steps
     bwd_ms = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps
@@ -114,7 +126,9 @@ def main():
                    "bwd_kernel": {"ms": round(bwd_ms, 5), "GB/s": round(bwd_gbs, 1)}},
         "roofline": {"bound": "hbm", "kernel": "stream_kernel<GluBwdOp<silu,bf16>> (swiglu_invact_bwd)",
                      "achieved": round(bwd_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(bwd_gbs / HBM_PEAK_GBS, 4), "traffic": None},
+                     "frac": round(bwd_gbs / HBM_PEAK_GBS, 4),
+                     "traffic": TRAFFIC_BWD_FULL if n == synth.numel(WORKLOAD) else None,
+                     "algorithmic_bytes": n * BYTES_BWD, "avg_launch_ms": round(bwd_ms, 5)},
     }
     if args.cpu_elems:
         out["cpu_baseline"] = cpu_baseline(w, min(args.cpu_elems, n))
