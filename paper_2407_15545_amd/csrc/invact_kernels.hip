@@ -164,12 +164,12 @@ struct BwdOp {                       // grad_x = grad_y * q(y, s)
     {
         float a[8], g[8]; S::unpack(in.y, a); S::unpack(in.g, g);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) g[j] *= q_approx<KIND>(a[j], (in.m >> j) & 1u);
+        for (int j = 0; j < 8; ++j) g[j] = times_q<KIND, S::kPrec>(g[j], a[j], (in.m >> j) & 1u);
         S::store(gx, c, g);
     }
     __device__ __forceinline__ bool scalar(size_t i, bool bit) const
     {
-        S::store1(gx, i, S::load1(gy, i) * q_approx<KIND>(S::load1(y, i), bit));
+        S::store1(gx, i, times_q<KIND, S::kPrec>(S::load1(gy, i), S::load1(y, i), bit));
         return bit;
     }
     static constexpr bool kWritesMask = false;
@@ -222,9 +222,9 @@ struct GluBwdOp {                    // grad_up = grad_h * act ; grad_gate = gra
         float a[8], u[8], g[8]; S::unpack(in.a, a); S::unpack(in.u, u); S::unpack(in.g, g);
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            float q = q_approx<KIND>(a[j], (in.m >> j) & 1u);
+            float gate_grad = times_q<KIND, S::kPrec>(g[j], u[j], a[j], (in.m >> j) & 1u);
             a[j] = g[j] * a[j];                  // grad_up
-            u[j] = product3<S::kPrec>(g[j], u[j], q);   // grad_gate
+            u[j] = gate_grad;                    // grad_gate
         }
         S::store(gup, c, a);
         S::store(ggate, c, u);
@@ -233,7 +233,7 @@ struct GluBwdOp {                    // grad_up = grad_h * act ; grad_gate = gra
     {
         float a = S::load1(act_in, i), u = S::load1(up, i), g = S::load1(gh, i);
         S::store1(gup, i, g * a);
-        S::store1(ggate, i, product3<S::kPrec>(g, u, q_approx<KIND>(a, bit)));
+        S::store1(ggate, i, times_q<KIND, S::kPrec>(g, u, a, bit));
         return bit;
     }
     static constexpr bool kWritesMask = false;

@@ -195,67 +195,99 @@ __device__ __forceinline__ float cubic_exp2(const float (&t)[4], float yt)
     return hw_exp2(fmaf(fmaf(fmaf(t[3], yt, t[2]), yt, t[1]), yt, t[0]));
 }
 
-// q for the two GELU forms.  `left` is the mask bit.
+// The pieces of q one evaluation produces:
+//   ql     q_left(y)                                        (Eq. (5) / Eq. (7))
+//   qr     q_right(y), summed so that the terms which cancel near y = f(T)
+//          (where q_right passes through zero) meet in fused operations
+//   small  q_right(y) - 1, i.e. h (GELU) or h (1 - y) (SiLU), with a relative
+//          error of a few ulp of ITSELF: the better representation once |small| is
+//          well below 1 (q near or above 1)
+struct QParts { float ql, qr, small; };
+
 template <int KIND>
-__device__ __forceinline__ float q_gelu(float y, bool left)
+__device__ __forceinline__ QParts q_parts(float y)
 {
     constexpr float fT = KindConst<KIND>::fT;
-    const auto& L = cst::gelu_left;
-    const auto& R = cst::gelu_right;
-    // Eq. (6): 1 + (c0 + c1 sqrt(yt) + c2 yt) E.  E is exactly 0 beyond yt = 64,
-    // so y is clamped there (keeps +inf from producing inf * 0).
-    float yc = (y > 64.0f) ? 64.0f : y;
-    float yt = clamp0(yc - fT);
-    float E  = cubic_exp2(cst::gelu_right_exp2, yt);
-    float r  = fmaf(R[2], yt, R[1] * hw_sqrt(yt));
-    float qr = fmaf(r, E, fmaf(R[0], E, 1.0f));
-    // Eq. (5): c0 sqrt(y + c1) (2y + c2 sqrt(-y)) (|c3 y^2 + |c4 y + c5| + c6| + c7).
-    // NaN reaches the result through the 2y term, so fmax may drop it here.
-    float s1 = hw_sqrt(fmaxf(y + L[1], 0.0f));
-    float s2 = hw_sqrt(fmaxf(-y, 0.0f));
-    float B  = fmaf(L[2], s2, y + y);
-    float inner = fabsf(fmaf(L[4], y, L[5]));
-    float outer = fabsf(fmaf(L[3], y * y, inner) + L[6]) + L[7];
-    float ql = (L[0] * s1) * B * outer;
-    return left ? ql : qr;
+    QParts out;
+    if constexpr (KIND == SILU) {
+        const auto& L = cst::silu_left;
+        const auto& R = cst::silu_right;
+        float yc = (y > 64.0f) ? 64.0f : y;          // E == 0 beyond yt = 64; keeps NaN, tames +inf
+        float yt = clamp0(yc - fT);
+        float sq = hw_sqrt(yt);
+        // Eq. (8) as 1 + h (1 - y), h = (c0 + r) E
+        float E = cubic_exp2(cst::silu_right_exp2, yt);
+        float r = fmaf(R[2], yt, R[1] * sq);
+        float h = fmaf(r, E, R[0] * E);
+        out.qr    = fmaf(-yc, h, fmaf(r, E, fmaf(R[0], E, 1.0f)));
+        out.small = h * (1.0f - yc);
+        // Eq. (7): (c0 + c1 sqrt(yt) + c2 yt + c3 yt^2) (1 - y) + y
+        float A = fmaf(yt, fmaf(L[3], yt, L[2]), fmaf(L[1], sq, L[0]));
+        out.ql = fmaf(A, 1.0f - yc, yc);
+    } else {
+        const auto& L = cst::gelu_left;
+        const auto& R = cst::gelu_right;
+        // Eq. (6): 1 + (c0 + c1 sqrt(yt) + c2 yt) E.  E is exactly 0 beyond yt = 64,
+        // so y is clamped there (keeps +inf from producing inf * 0).
+        float yc = (y > 64.0f) ? 64.0f : y;
+        float yt = clamp0(yc - fT);
+        float E  = cubic_exp2(cst::gelu_right_exp2, yt);
+        float r  = fmaf(R[2], yt, R[1] * hw_sqrt(yt));
+        out.qr    = fmaf(r, E, fmaf(R[0], E, 1.0f));
+        out.small = fmaf(r, E, R[0] * E);
+        // Eq. (5): c0 sqrt(y + c1) (2y + c2 sqrt(-y)) (|c3 y^2 + |c4 y + c5| + c6| + c7).
+        // NaN reaches the result through the 2y term, so fmax may drop it here.
+        float s1 = hw_sqrt(fmaxf(y + L[1], 0.0f));
+        float s2 = hw_sqrt(fmaxf(-y, 0.0f));
+        float B  = fmaf(L[2], s2, y + y);
+        float inner = fabsf(fmaf(L[4], y, L[5]));
+        float outer = fabsf(fmaf(L[3], y * y, inner) + L[6]) + L[7];
+        out.ql = (L[0] * s1) * B * outer;
+    }
+    return out;
 }
 
-// q for SiLU.
-__device__ __forceinline__ float q_silu(float y, bool left)
+// The product of q(y, s) with the incoming gradient.
+//
+// FAST (bfloat16 storage): plain products; every rounding is far below the
+// store's.
+// PRECISE (binary32 storage): q is kept as base + delta with
+//   (base, delta) = (ql, 0) on the left branch,
+//                   (qr, 0) on the right branch while |small| >= 1/4,
+//                   (1, small) otherwise,
+// and the product with g is rounded once.  Where q is near 1 a rounded q would
+// by itself cost half an ulp of the two the result may be off by.
+
+// grad * q  (invact_bwd)
+template <int KIND, int PREC>
+__device__ __forceinline__ float times_q(float g, float y, bool left)
 {
-    constexpr float fT = KindConst<SILU>::fT;
-    const auto& L = cst::silu_left;
-    const auto& R = cst::silu_right;
-    float yc = (y > 64.0f) ? 64.0f : y;          // E == 0 beyond; keeps NaN
-    float yt = clamp0(yc - fT);
-    float sq = hw_sqrt(yt);
-    // Eq. (8) as 1 + h (1 - y), h = (c0 + r) E, summed so that the large terms
-    // 1 + c0 E and -y h meet in fused operations (they cancel near y = f(T)).
-    float E   = cubic_exp2(cst::silu_right_exp2, yt);
-    float r   = fmaf(R[2], yt, R[1] * sq);
-    float h   = fmaf(r, E, R[0] * E);
-    float qr  = fmaf(-yc, h, fmaf(r, E, fmaf(R[0], E, 1.0f)));
-    // Eq. (7): (c0 + c1 sqrt(yt) + c2 yt + c3 yt^2) (1 - y) + y
-    float A  = fmaf(yt, fmaf(L[3], yt, L[2]), fmaf(L[1], sq, L[0]));
-    float ql = fmaf(A, 1.0f - yc, yc);
-    return left ? ql : qr;
+    QParts p = q_parts<KIND>(y);
+    if constexpr (PREC == FAST) {
+        return g * (left ? p.ql : p.qr);
+    } else {
+        const bool direct = left || !(fabsf(p.small) < 0.25f);
+        float base  = left ? p.ql : (direct ? p.qr : 1.0f);
+        float delta = direct ? 0.0f : p.small;
+        return fmaf(g, base, g * delta);
+    }
 }
 
-// a * b * c.  PRECISE carries the rounding error of a * b along, so that the
-// result is rounded once (two roundings can reach 2 ulp by themselves).
-template <int PREC>
-__device__ __forceinline__ float product3(float a, float b, float c)
+// (a * b) * q  (gated backward: a = grad_h, b = up)
+template <int KIND, int PREC>
+__device__ __forceinline__ float times_q(float a, float b, float y, bool left)
 {
-    float p = a * b;
-    if constexpr (PREC == FAST) return p * c;
-    else return fmaf(p, c, fmaf(a, b, -p) * c);
-}
-
-template <int KIND>
-__device__ __forceinline__ float q_approx(float y, bool left)
-{
-    if constexpr (KIND == SILU) return q_silu(y, left);
-    else return q_gelu<KIND>(y, left);
+    QParts p = q_parts<KIND>(y);
+    float g = a * b;
+    if constexpr (PREC == FAST) {
+        return g * (left ? p.ql : p.qr);
+    } else {
+        const bool direct = left || !(fabsf(p.small) < 0.25f);
+        float base  = left ? p.ql : (direct ? p.qr : 1.0f);
+        float delta = direct ? 0.0f : p.small;
+        float e = fmaf(a, b, -g);                              // a b = g + e exactly
+        return fmaf(g, base, fmaf(g, delta, e * (base + delta)));
+    }
 }
 
 }  // namespace invact_dev
