@@ -2,17 +2,25 @@
 // the contract of every entry point.
 //
 // Kernel shape.  All four kernels are pure streaming maps, bound by HBM
-// bandwidth, so they share one skeleton: a grid of 256-thread workgroups
-// (a few per compute unit) strides over the tensor in "chunks" of 8
-// consecutive elements per lane.  8 elements are one 128-bit access for
-// bfloat16 (two for binary32) and exactly one byte of the branch mask, so a
-// lane owns its mask byte outright: the canonical little-endian bit stream
-// comes out of lane-local shifts, no cross-lane traffic, and a wavefront
-// writes 64 consecutive mask bytes (eight 64-bit words) per step.  Each lane
-// keeps kUnroll independent chunks in flight: all loads of a step are issued
+// bandwidth, so they share one skeleton.  The unit of work of a wavefront is a
+// "wave tile" of 512 consecutive elements = 64 mask bytes = eight 64-bit mask
+// words; each lane owns 8 of those elements (its "chunk"):
+//   bfloat16  lane L owns elements 8L .. 8L+7: one 128-bit access, and exactly
+//             mask byte L of the tile;
+//   binary32  lane L owns elements 4L .. 4L+3 and 256+4L .. 256+4L+3: two
+//             128-bit accesses, each fully coalesced across the wavefront (1 KiB
+//             contiguous; letting a lane own 32 contiguous bytes instead costs
+//             10-19 % of the bandwidth).  A lane then holds two nibbles of two
+//             different mask bytes; neighbouring lanes swap nibbles with one
+//             DPP move so that every lane again stores (or loads) one byte.
+// The canonical little-endian bit stream thus comes out of lane-local shifts.
+// Each lane keeps kUnroll chunks in flight: all loads of a step are issued
 // before the first store, which is also what makes element-wise in-place use
-// (y == x and the like) safe.  The < 8 elements past the last full chunk and
-// the zero padding of the last mask word are written by one thread.
+// (y == x and the like) safe.  By default a workgroup handles one tile of
+// kUnroll * 256 chunks and retires; every global access is non-temporal (each
+// byte is touched once).  The up to 511 elements past the last full wave tile
+// are handled one element per lane by the first wavefront, the mask word being
+// formed by a wave64 ballot there (and zero padding coming for free).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -36,6 +44,7 @@ using namespace invact_dev;
 #endif
 
 constexpr int  kThreads = 256;
+constexpr int  kWaveTile = 512;                   // elements per wavefront and step
 constexpr int  kUnroll  = INVACT_UNROLL;          // chunks in flight per lane
 constexpr bool kNonTemporal = INVACT_NT != 0;     // every byte is touched once: keep it out of the caches
 constexpr int  kDefaultBlocksPerCu = INVACT_DEFAULT_BLOCKS_PER_CU;   // 0: one tile per workgroup
@@ -49,13 +58,21 @@ template <class T> __device__ __forceinline__ void st(T* p, T v)
     if constexpr (kNonTemporal) __builtin_nontemporal_store(v, p); else *p = v;
 }
 
+// value of the neighbouring lane (lane ^ 1); every lane of the quad must be active
+__device__ __forceinline__ uint32_t swap_with_neighbour(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1 /* quad_perm [1,0,3,2] */, 0xF, 0xF, true);
+}
+
 typedef float    f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16   bf16x2 __attribute__((ext_vector_type(2)));
 typedef float    f32x2 __attribute__((ext_vector_type(2)));
 
 // ---------------------------------------------------------------------------
-// Storage formats: 8 elements <-> 8 floats in registers
+// Storage formats: one chunk (8 elements of one lane) <-> 8 floats in
+// registers, and the chunk's 8 mask bits <-> memory.  `c` is the global chunk
+// index: wave tile c / 64, lane c % 64.
 // ---------------------------------------------------------------------------
 
 template <int DT> struct Storage;
@@ -63,20 +80,42 @@ template <int DT> struct Storage;
 template <> struct Storage<INVACT_FP32> {
     struct Raw { f32x4 a, b; };
     static constexpr int kPrec = PRECISE;
-    static __device__ __forceinline__ Raw load(const void* p, size_t chunk)
+    // v[0..3] = elements 4L.., v[4..7] = elements 256 + 4L.. of the wave tile
+    static __device__ __forceinline__ size_t vec_index(size_t c) { return (c >> 6) * 128 + (c & 63); }
+    static __device__ __forceinline__ Raw load(const void* p, size_t c)
     {
-        const f32x4* q = reinterpret_cast<const f32x4*>(p) + 2 * chunk;
-        return Raw{ld(q), ld(q + 1)};
+        const f32x4* q = reinterpret_cast<const f32x4*>(p) + vec_index(c);
+        return Raw{ld(q), ld(q + 64)};
     }
     static __device__ __forceinline__ void unpack(const Raw& r, float (&v)[8])
     {
         for (int j = 0; j < 4; ++j) { v[j] = r.a[j]; v[4 + j] = r.b[j]; }
     }
-    static __device__ __forceinline__ void store(void* p, size_t chunk, const float (&v)[8])
+    static __device__ __forceinline__ void store(void* p, size_t c, const float (&v)[8])
     {
-        f32x4* q = reinterpret_cast<f32x4*>(p) + 2 * chunk;
+        f32x4* q = reinterpret_cast<f32x4*>(p) + vec_index(c);
         st(q, f32x4{v[0], v[1], v[2], v[3]});
-        st(q + 1, f32x4{v[4], v[5], v[6], v[7]});
+        st(q + 64, f32x4{v[4], v[5], v[6], v[7]});
+    }
+    // Bits 0-3 of m belong to byte L/2 of the tile (low nibble for even L), bits
+    // 4-7 to byte 32 + L/2.  Even lanes end up with the first byte of the pair,
+    // odd lanes with the second.
+    static __device__ __forceinline__ size_t mask_index(size_t c)
+    {
+        return (c >> 6) * 64 + ((c & 1) ? 32 : 0) + ((c & 63) >> 1);
+    }
+    static __device__ __forceinline__ void store_mask(uint8_t* mask, size_t c, uint32_t m)
+    {
+        const uint32_t other = swap_with_neighbour(m);
+        const uint32_t byte = (c & 1) ? (((other >> 4) & 0xFu) | (m & 0xF0u))
+                                      : ((m & 0xFu) | ((other & 0xFu) << 4));
+        st(mask + mask_index(c), (uint8_t)byte);
+    }
+    static __device__ __forceinline__ uint32_t load_mask(const uint8_t* mask, size_t c)
+    {
+        const uint32_t own = ld(mask + mask_index(c));
+        const uint32_t other = swap_with_neighbour(own);
+        return (c & 1) ? ((other >> 4) | (own & 0xF0u)) : ((own & 0xFu) | ((other & 0xFu) << 4));
     }
     static __device__ __forceinline__ float load1(const void* p, size_t i) { return reinterpret_cast<const float*>(p)[i]; }
     static __device__ __forceinline__ void store1(void* p, size_t i, float v) { reinterpret_cast<float*>(p)[i] = v; }
@@ -85,9 +124,9 @@ template <> struct Storage<INVACT_FP32> {
 template <> struct Storage<INVACT_BF16> {
     struct Raw { u32x4 w; };
     static constexpr int kPrec = FAST;
-    static __device__ __forceinline__ Raw load(const void* p, size_t chunk)
+    static __device__ __forceinline__ Raw load(const void* p, size_t c)
     {
-        return Raw{ld(reinterpret_cast<const u32x4*>(p) + chunk)};
+        return Raw{ld(reinterpret_cast<const u32x4*>(p) + c)};
     }
     static __device__ __forceinline__ void unpack(const Raw& r, float (&v)[8])
     {
@@ -101,11 +140,13 @@ template <> struct Storage<INVACT_BF16> {
     {
         return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo, hi}, bf16x2));
     }
-    static __device__ __forceinline__ void store(void* p, size_t chunk, const float (&v)[8])
+    static __device__ __forceinline__ void store(void* p, size_t c, const float (&v)[8])
     {
-        st(reinterpret_cast<u32x4*>(p) + chunk,
+        st(reinterpret_cast<u32x4*>(p) + c,
            u32x4{pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7])});
     }
+    static __device__ __forceinline__ void store_mask(uint8_t* mask, size_t c, uint32_t m) { st(mask + c, (uint8_t)m); }
+    static __device__ __forceinline__ uint32_t load_mask(const uint8_t* mask, size_t c) { return ld(mask + c); }
     static __device__ __forceinline__ float load1(const void* p, size_t i)
     {
         return __uint_as_float((uint32_t) reinterpret_cast<const uint16_t*>(p)[i] << 16);
@@ -121,7 +162,7 @@ template <> struct Storage<INVACT_BF16> {
 //   In      -- the raw registers of one chunk of every input stream
 //   load    -- fill In for chunk c
 //   run     -- compute and store chunk c
-//   scalar  -- the same for the single element i (tail), returning the mask bit
+//   scalar  -- the same for the single element i (tail); takes / returns the mask bit
 // ---------------------------------------------------------------------------
 
 template <int KIND, int DT>
@@ -140,7 +181,7 @@ struct FwdOp {                       // y = f(x), s = [x < T]
             v[j] = act<KIND, S::kPrec>(v[j]);
         }
         S::store(y, c, v);
-        st(mask + c, (uint8_t)m);
+        S::store_mask(mask, c, m);
     }
     __device__ __forceinline__ bool scalar(size_t i, bool) const
     {
@@ -158,7 +199,7 @@ struct BwdOp {                       // grad_x = grad_y * q(y, s)
     struct In { typename S::Raw y, g; uint32_t m; };
     __device__ __forceinline__ void load(In& in, size_t c) const
     {
-        in.y = S::load(y, c); in.g = S::load(gy, c); in.m = ld(mask + c);
+        in.y = S::load(y, c); in.g = S::load(gy, c); in.m = S::load_mask(mask, c);
     }
     __device__ __forceinline__ void run(const In& in, size_t c) const
     {
@@ -195,7 +236,7 @@ struct GluFwdOp {                    // act = f(gate), s = [gate < T], h = f(gat
         }
         S::store(act_out, c, v);
         S::store(h, c, u);
-        st(mask + c, (uint8_t)m);
+        S::store_mask(mask, c, m);
     }
     __device__ __forceinline__ bool scalar(size_t i, bool) const
     {
@@ -215,7 +256,7 @@ struct GluBwdOp {                    // grad_up = grad_h * act ; grad_gate = gra
     struct In { typename S::Raw a, u, g; uint32_t m; };
     __device__ __forceinline__ void load(In& in, size_t c) const
     {
-        in.a = S::load(act_in, c); in.u = S::load(up, c); in.g = S::load(gh, c); in.m = ld(mask + c);
+        in.a = S::load(act_in, c); in.u = S::load(up, c); in.g = S::load(gh, c); in.m = S::load_mask(mask, c);
     }
     __device__ __forceinline__ void run(const In& in, size_t c) const
     {
@@ -246,10 +287,14 @@ struct GluBwdOp {                    // grad_up = grad_h * act ; grad_gate = gra
 // PERSISTENT: the grid strides over the chunks (a fixed number of workgroups
 // per compute unit).  Otherwise every workgroup handles one tile of
 // kUnroll * kThreads chunks and retires, and the dispatcher balances the load.
+// The number of chunks is a multiple of 64, so a wavefront is either entirely
+// inside the tensor or entirely outside: every branch below is wave-uniform
+// (the neighbour swap of the binary32 mask needs whole quads).
 template <class Op, bool PERSISTENT>
 __global__ __launch_bounds__(kThreads) void stream_kernel(const Op op, const size_t n)
 {
-    const size_t chunks = n / 8;
+    const size_t wave_tiles = n / kWaveTile;
+    const size_t chunks = wave_tiles * 64;
 
     if constexpr (PERSISTENT) {
         const size_t stride = (size_t)gridDim.x * kThreads;
@@ -286,25 +331,21 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(const Op op, const siz
         }
     }
 
-    // Tail: elements [8 chunks, n) and, in the forward kernels, the rest of the
-    // last 64-bit mask word.
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
-        const size_t first = chunks * 8;
-        if (first < n) {
-            const uint8_t* mask_in = nullptr;
-            if constexpr (!Op::kWritesMask) mask_in = op.mask;
-            uint32_t m = 0;
-            for (size_t i = first; i < n; ++i) {
+    // Tail: elements [512 wave_tiles, n), one per lane, by the first wavefront.
+    // Whole 64-bit mask words are written (read), so the zero padding of the
+    // last word comes from the ballot itself.
+    if (blockIdx.x == 0 && threadIdx.x < 64) {
+        for (size_t base = wave_tiles * kWaveTile; base < n; base += 64) {
+            const size_t i = base + threadIdx.x;
+            if constexpr (Op::kWritesMask) {
                 bool bit = false;
-                if constexpr (!Op::kWritesMask) bit = (mask_in[chunks] >> (i - first)) & 1u;
-                m |= (uint32_t)op.scalar(i, bit) << (i - first);
+                if (i < n) bit = op.scalar(i, false);
+                const uint64_t word = __builtin_amdgcn_ballot_w64(bit);
+                if (threadIdx.x == 0) reinterpret_cast<uint64_t*>(op.mask)[base / 64] = word;
+            } else {
+                const uint64_t word = reinterpret_cast<const uint64_t*>(op.mask)[base / 64];
+                if (i < n) op.scalar(i, (word >> threadIdx.x) & 1u);
             }
-            if constexpr (Op::kWritesMask) op.mask[chunks] = (uint8_t)m;
-        }
-        if constexpr (Op::kWritesMask) {
-            const size_t used  = (n + 7) / 8;
-            const size_t total = 8 * ((n + 63) / 64);
-            for (size_t b = used; b < total; ++b) op.mask[b] = 0;
         }
     }
 }
@@ -333,7 +374,7 @@ bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) &
 template <class Op>
 int launch(const Op& op, size_t n, hipStream_t stream)
 {
-    const size_t chunks = n / 8;
+    const size_t chunks = (n / kWaveTile) * 64;
     const int per_cu = g_blocks_per_cu.load(std::memory_order_relaxed);
     if (per_cu == 0) {
         size_t blocks = (chunks + kThreads * kUnroll - 1) / (kThreads * kUnroll);

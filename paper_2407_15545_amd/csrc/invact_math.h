@@ -1,16 +1,21 @@
 // Device-side arithmetic of the Inverted-Activations kernels (gfx950).
 //
-// Everything here works on binary32 values in registers.  Two precision
-// policies exist for the forward activation:
-//   FAST    -- hardware exp2 / rcp / sqrt (1 ulp each) and short polynomials;
-//              far more accurate than a bfloat16 store can show.  Used when
-//              the storage dtype is bfloat16.
-//   PRECISE -- arguments and the final combination in binary64, the
-//              transcendental itself still the binary32 hardware unit fed
-//              with a hi + lo split argument; about 1.6 ulp worst case.  Used
-//              when the storage dtype is binary32.
-// The backward approximation q (Eqs. (5)-(8)) is evaluated the same way for
-// both dtypes: its absolute error is what matters there.
+// Two precision policies exist for the forward activation:
+//   FAST    -- binary32 throughout, hardware exp2 / rcp / sqrt (each within one
+//              ulp) and short polynomials; far more accurate than a bfloat16
+//              store can show.  Used when the storage dtype is bfloat16.
+//   PRECISE -- arguments and the final combination in binary64 (full rate on
+//              this chip), the transcendental itself still the binary32 unit,
+//              fed with the fractional part of a hi + lo split argument; one
+//              rounding to binary32 at the end.  Used when the storage dtype is
+//              binary32, where a binary32 exponent argument alone would cost
+//              5-70 ulp in the left tail.
+// The backward approximation q (Eqs. (5)-(8)) is evaluated in binary32 for both
+// dtypes; for binary32 storage its product with the gradient is rounded once.
+//
+// Rough cost model measured on MI355X (lanes per clock and compute unit):
+// v_add/mul/fma_f32 ~100, other VALU incl. binary64 fma/mul/add and conversions
+// ~60, v_exp/rcp/sqrt_f32 ~31, v_rcp_f64 ~16.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -28,17 +33,15 @@ namespace cst = invact_const;
 __device__ __forceinline__ float hw_exp2(float v) { return __builtin_amdgcn_exp2f(v); }   // v_exp_f32
 __device__ __forceinline__ float hw_rcp(float v)  { return __builtin_amdgcn_rcpf(v); }    // v_rcp_f32
 __device__ __forceinline__ float hw_sqrt(float v) { return __builtin_amdgcn_sqrtf(v); }   // v_sqrt_f32
-__device__ __forceinline__ float clamp_finite(float v)                                    // NaN -> -FLT_MAX
-{
-    return __builtin_amdgcn_fmed3f(v, -FLT_MAX, FLT_MAX);
-}
+// median of three: clamps v to [lo, hi]; a NaN comes out as lo
+__device__ __forceinline__ float med3(float v, float lo, float hi) { return __builtin_amdgcn_fmed3f(v, lo, hi); }
 
-constexpr float kLog2e      = 1.44269504088896340736f;
-constexpr double kLog2eD    = 1.44269504088896340736;
-constexpr double kLn2D      = 0.69314718055994530942;
+constexpr float  kLog2e       = 1.44269504088896340736f;
+constexpr double kLog2eD      = 1.44269504088896340736;
+constexpr double kLn2D        = 0.69314718055994530942;
 constexpr double kSqrt2OverPi = 0.79788456080286535588;   // sqrt(2/pi)
-constexpr double kGeluCubic = 0.044715;
-constexpr double kInvSqrt2  = 0.70710678118654752440;
+constexpr double kGeluCubic   = 0.044715;
+constexpr double kInvSqrt2    = 0.70710678118654752440;
 
 // The branch threshold T (minimiser of f) and f(T), rounded to binary32.
 template <int KIND> struct KindConst;
@@ -46,126 +49,110 @@ template <> struct KindConst<GELU_TANH> { static constexpr float T = cst::T_gelu
 template <> struct KindConst<GELU_ERF>  { static constexpr float T = cst::T_gelu_erf,  fT = cst::fT_gelu_erf; };
 template <> struct KindConst<SILU>      { static constexpr float T = cst::T_silu,      fT = cst::fT_silu; };
 
+// All three activations are written as
+//     f(x) = max(x, -0) - |u|,   u = x * P(-|x|),
+// with P the gate evaluated on the negative side (sigmoid(-|z|) or Phi(-|x|)):
+// for x < 0 this is u itself, for x >= 0 it is x - x P(-|x|) = x P(|x|).  One
+// formula, no select, and -inf, -0 and +inf come out as -0, -0 and +inf.
+
 // ---------------------------------------------------------------------------
 // Forward, FAST
 // ---------------------------------------------------------------------------
 
-// x * sigmoid(z) given th = -|z| log2(e) / 2 (sign(z) = sign(x)).
-// With Eh = exp(-|z|/2):  sigmoid(|z|) = 1 / (1 + Eh^2),  sigmoid(-|z|) = Eh^2 / (1 + Eh^2).
-// The product is taken as (x Eh) * (Eh r) so that no factor is subnormal
-// while the result is still a normal number (x ~ -90 for SiLU).
-__device__ __forceinline__ float x_sigmoid_fast(float x, float th)
+// x * sigmoid(-|z|) from th = -|z| log2(e) / 2.  With Eh = exp(-|z|/2) the gate
+// is Eh^2 / (1 + Eh^2); the product is taken as (x Eh) * (Eh r) so that no
+// factor is subnormal while the result is still a normal number (x ~ -90 for
+// SiLU).  A NaN x arrives through th.
+__device__ __forceinline__ float x_gate_fast(float x, float th)
 {
     float Eh = hw_exp2(th);
     float r  = hw_rcp(fmaf(Eh, Eh, 1.0f));
-    float m  = (x < 0.0f) ? Eh : 1.0f;
-    float a  = clamp_finite(x) * m;          // -inf * 0 must not make a NaN; NaN x comes back through r
-    return a * (r * m);
+    return (med3(x, -FLT_MAX, FLT_MAX) * Eh) * (Eh * r);
 }
 
 template <int KIND>
 __device__ __forceinline__ float act_fast(float x)
 {
+    float u;
     if constexpr (KIND == SILU) {
-        return x_sigmoid_fast(x, -fabsf(x) * (0.5f * kLog2e));
+        u = x_gate_fast(x, -fabsf(x) * (0.5f * kLog2e));
     } else if constexpr (KIND == GELU_TANH) {
-        // z = 2u, u = sqrt(2/pi) (x + 0.044715 x^3):  |z| log2(e) / 2 = |x (k1 + k2 x^2)|
+        // z = 2u', u' = sqrt(2/pi) (x + 0.044715 x^3):  |z| log2(e) / 2 = |x (k1 + k2 x^2)|
         constexpr float k1 = (float)(kSqrt2OverPi * kLog2eD);
         constexpr float k2 = (float)(kSqrt2OverPi * kLog2eD * kGeluCubic);
-        float inner = x * fmaf(k2, x * x, k1);
-        return x_sigmoid_fast(x, -fabsf(inner));
+        u = x_gate_fast(x, -fabsf(x * fmaf(k2, x * x, k1)));
     } else {
-        // x Phi(x), Phi(-|x|) = erfc(z)/2 = erfcx(z) exp(-z^2) / 2 with z = |x| / sqrt 2
+        // Phi(-|x|) = erfc(z) / 2 = erfcx(z) exp(-z^2) / 2 with z = |x| / sqrt 2
         constexpr float pz = (float)(cst::erfcx_fast_p * kInvSqrt2);
-        float ax = fabsf(x);
-        float w  = hw_rcp(fmaf(pz, ax, 1.0f));
-        float g  = 0.5f * cst::erfcx_fast[5];
+        float w = hw_rcp(fmaf(pz, fabsf(x), 1.0f));
+        float g = 0.5f * cst::erfcx_fast[5];
 #pragma unroll
         for (int k = 4; k >= 0; --k) g = fmaf(g, w, 0.5f * cst::erfcx_fast[k]);
-        g *= w;                                                   // erfcx(z) / 2
         float E = hw_exp2((x * x) * (-0.5f * kLog2e));            // exp(-z^2)
-        float u = (clamp_finite(x) * g) * E;                      // x Phi(-|x|) sign-carrying
-        return (x < 0.0f) ? u : x - u;                            // x (1 - Phi(-|x|)) for x >= 0
+        u = (med3(x, -FLT_MAX, FLT_MAX) * (g * w)) * E;
     }
+    return fmaxf(x, -0.0f) - fabsf(u);
 }
 
 // ---------------------------------------------------------------------------
 // Forward, PRECISE
 // ---------------------------------------------------------------------------
 
-// exp2 of a binary64 argument t <= 0 through the binary32 unit:
-// 2^t = 2^hi * 2^lo,  hi = fl32(t),  2^lo = 1 + lo ln2 (|lo| < 2^-24 |t|).
-// Returns a binary64 value with the relative error of v_exp_f32 (1 ulp of
-// binary32) and no error from the argument.  `bias` is added to the
-// exponent so that the caller can keep the result normal.
-__device__ __forceinline__ double exp2_split(double t, float bias)
+// 2^t for a binary64 t in [-30000, 0]:  t = hi + lo with hi = fl32(t);
+// 2^hi = 2^n 2^f with n = round(hi), f in [-1/2, 1/2] (exact in binary32), 2^f
+// from v_exp_f32, 2^lo = 1 + lo ln2, and the scaling by 2^n exact in binary64
+// (no subnormal binary32 intermediate).  Relative error: that of v_exp_f32.
+__device__ __forceinline__ double exp2_neg(double t)
 {
     float hi = (float)t;
-    float lo = (float)(t - (double)hi);
-    float e  = hw_exp2(hi + bias);
-    return (double)e * (1.0 + kLn2D * (double)lo);
+    float n  = __builtin_rintf(hi);
+    float e  = hw_exp2(hi - n);
+    double c = fma(kLn2D, t - (double)hi, 1.0);
+    return ldexp((double)e * c, (int)n);
 }
 
-// 1 / d for d in [1, 2], to ~2^-45: binary32 seed and one Newton step in binary64.
+// 1 / d for d in [1, 16], to about 2^-44: binary32 seed, one Newton step in binary64.
 __device__ __forceinline__ double rcp_newton(double d)
 {
     double r = (double)hw_rcp((float)d);
-    return r * (2.0 - d * r);
+    return r * fma(-d, r, 2.0);
 }
 
-// x * sigmoid(z) with t = -|z| log2(e) given in binary64; result in binary64
-// (relative error about 2^-23.3 from the hardware exp2, nothing else).
-__device__ __forceinline__ double x_sigmoid_precise(float x, double t)
-{
-    // E = exp(-|z|) scaled by 2^64 when it would be subnormal in binary32
-    t = (t < -300.0) ? -300.0 : t;                 // keeps fl32(t) finite; NaN stays NaN
-    const bool tiny = t < -120.0;
-    double E = exp2_split(t, tiny ? 64.0f : 0.0f);
-    double Eu = tiny ? 0.0 : E;                    // unscaled value, only needed in 1 + E
-    double r = rcp_newton(1.0 + Eu);
-    double xd = (double)clamp_finite(x);
-    double y = (x < 0.0f) ? xd * E * r * (tiny ? 0x1p-64 : 1.0) : xd * r;
-    return (x == INFINITY) ? (double)x : y;
-}
-
+// f(x) in binary64, not yet protected against a NaN x (see nan_through).
 template <int KIND>
 __device__ __forceinline__ double act_precise(float x)
 {
+    double u;
     if constexpr (KIND == SILU) {
-        return x_sigmoid_precise(x, -fabs((double)x) * kLog2eD);
+        double xd = (double)med3(x, -2048.0f, 2048.0f);        // beyond, the gate underflows to 0 anyway
+        double E  = exp2_neg(-fabs(xd) * kLog2eD);
+        u = xd * E * rcp_newton(1.0 + E);
     } else if constexpr (KIND == GELU_TANH) {
-        double xd = (double)x;
-        double z2 = xd * (2.0 * kSqrt2OverPi * kLog2eD + (2.0 * kSqrt2OverPi * kLog2eD * kGeluCubic) * (xd * xd));
-        return x_sigmoid_precise(x, -fabs(z2));
+        constexpr double a = 2.0 * kSqrt2OverPi * kLog2eD, b = a * kGeluCubic;
+        double xd = (double)med3(x, -64.0f, 64.0f);
+        double E  = exp2_neg(-fabs(xd * fma(b, xd * xd, a)));
+        u = xd * E * rcp_newton(1.0 + E);
     } else {
-        if (fabsf(x) == INFINITY) return (x > 0.0f) ? (double)x : -0.0;
-        double ax = fabs((double)x);
-        double z  = ax * kInvSqrt2;
-        // w = 1 / (1 + p z) in (0, 1]; seed + Newton as above (the denominator is not in [1,2]
-        // but the binary32 seed is good to 2^-22 for any normal argument)
-        double d = 1.0 + cst::erfcx_precise_p * z;
-        double w = (double)hw_rcp((float)d);
-        w = w * (2.0 - d * w);
-        double g = cst::erfcx_precise[10];
+        double xd = (double)med3(x, -64.0f, 64.0f);
+        double w  = rcp_newton(fma(cst::erfcx_precise_p * kInvSqrt2, fabs(xd), 1.0));
+        double g  = 0.5 * cst::erfcx_precise[9];
 #pragma unroll
-        for (int k = 9; k >= 0; --k) g = g * w + cst::erfcx_precise[k];
-        g *= w;                                                    // erfcx(z)
-        double t = -(z * z) * kLog2eD;                             // log2 of exp(-z^2)
-        const bool tiny = t < -100.0;
-        double E = exp2_split(t < -300.0 ? -300.0 : t, tiny ? 64.0f : 0.0f);
-        double xd = (double)clamp_finite(x);
-        double u = xd * (0.5 * g) * E;                             // x erfc(z) / 2 (scaled if tiny)
-        if (tiny) u *= 0x1p-64;
-        return (x < 0.0f) ? u : (double)x - u;
+        for (int k = 8; k >= 0; --k) g = fma(g, w, 0.5 * cst::erfcx_precise[k]);
+        double E = exp2_neg((xd * xd) * (-0.5 * kLog2eD));
+        u = xd * (g * w) * E;
     }
+    return fmax((double)x, -0.0) - fabs(u);
 }
+
+// The clamps above drop a NaN; put it back.
+__device__ __forceinline__ float nan_through(float x, float v) { return (x != x) ? x : v; }
 
 // f(x) rounded once to binary32.
 template <int KIND, int PREC>
 __device__ __forceinline__ float act(float x)
 {
     if constexpr (PREC == FAST) return act_fast<KIND>(x);
-    else return (float)act_precise<KIND>(x);
+    else return nan_through(x, (float)act_precise<KIND>(x));
 }
 
 // f(gate) and f(gate) * up, each rounded once (the product is formed from the
@@ -178,16 +165,14 @@ __device__ __forceinline__ void act_times(float gate, float up, float& a, float&
         h = a * up;
     } else {
         double ad = act_precise<KIND>(gate);
-        a = (float)ad;
-        h = (float)(ad * (double)up);
+        a = nan_through(gate, (float)ad);
+        h = nan_through(gate, (float)(ad * (double)up));
     }
 }
 
 // ---------------------------------------------------------------------------
 // Backward: q(y, s) ~ f'(f^-1(y)), Eqs. (5)-(8)
 // ---------------------------------------------------------------------------
-
-__device__ __forceinline__ float clamp0(float v) { return (v < 0.0f) ? 0.0f : v; }   // NaN stays NaN
 
 // 2^(log2(e) c3 (c4 - yt)^3) by Horner's rule on the expanded cubic.
 __device__ __forceinline__ float cubic_exp2(const float (&t)[4], float yt)
@@ -200,20 +185,24 @@ __device__ __forceinline__ float cubic_exp2(const float (&t)[4], float yt)
 //   qr     q_right(y), summed so that the terms which cancel near y = f(T)
 //          (where q_right passes through zero) meet in fused operations
 //   small  q_right(y) - 1, i.e. h (GELU) or h (1 - y) (SiLU), with a relative
-//          error of a few ulp of ITSELF: the better representation once |small| is
-//          well below 1 (q near or above 1)
+//          error of a few ulp of ITSELF: the better representation once |small|
+//          is well below 1 (q near or above 1)
+// Clamps are NaN-dropping medians; the callers put a NaN y back.  yt is clamped
+// to [0, 64]: the exponential factor is exactly 0 beyond, and +inf must not
+// meet that 0.
 struct QParts { float ql, qr, small; };
 
 template <int KIND>
-__device__ __forceinline__ QParts q_parts(float y)
+__device__ __forceinline__ QParts q_parts(float y, bool left)
 {
     constexpr float fT = KindConst<KIND>::fT;
     QParts out;
     if constexpr (KIND == SILU) {
         const auto& L = cst::silu_left;
         const auto& R = cst::silu_right;
-        float yc = (y > 64.0f) ? 64.0f : y;          // E == 0 beyond yt = 64; keeps NaN, tames +inf
-        float yt = clamp0(yc - fT);
+        (void)left;
+        float yc = fminf(y, 64.0f);
+        float yt = med3(y - fT, 0.0f, 64.0f);
         float sq = hw_sqrt(yt);
         // Eq. (8) as 1 + h (1 - y), h = (c0 + r) E
         float E = cubic_exp2(cst::silu_right_exp2, yt);
@@ -227,22 +216,21 @@ __device__ __forceinline__ QParts q_parts(float y)
     } else {
         const auto& L = cst::gelu_left;
         const auto& R = cst::gelu_right;
-        // Eq. (6): 1 + (c0 + c1 sqrt(yt) + c2 yt) E.  E is exactly 0 beyond yt = 64,
-        // so y is clamped there (keeps +inf from producing inf * 0).
-        float yc = (y > 64.0f) ? 64.0f : y;
-        float yt = clamp0(yc - fT);
-        float E  = cubic_exp2(cst::gelu_right_exp2, yt);
-        float r  = fmaf(R[2], yt, R[1] * hw_sqrt(yt));
+        // Each element needs one of sqrt(y + c1) (Eq. (5)) and sqrt(y - f(T))
+        // (Eq. (6)): pick the addend by the branch bit and take one root.
+        float arg = med3(y + (left ? L[1] : -fT), 0.0f, 64.0f);
+        float sq  = hw_sqrt(arg);
+        // Eq. (6): 1 + (c0 + c1 sqrt(yt) + c2 yt) E, with yt = arg
+        float E = cubic_exp2(cst::gelu_right_exp2, arg);
+        float r = fmaf(R[2], arg, R[1] * sq);
         out.qr    = fmaf(r, E, fmaf(R[0], E, 1.0f));
         out.small = fmaf(r, E, R[0] * E);
-        // Eq. (5): c0 sqrt(y + c1) (2y + c2 sqrt(-y)) (|c3 y^2 + |c4 y + c5| + c6| + c7).
-        // NaN reaches the result through the 2y term, so fmax may drop it here.
-        float s1 = hw_sqrt(fmaxf(y + L[1], 0.0f));
+        // Eq. (5): c0 sqrt(y + c1) (2y + c2 sqrt(-y)) (|c3 y^2 + |c4 y + c5| + c6| + c7)
         float s2 = hw_sqrt(fmaxf(-y, 0.0f));
         float B  = fmaf(L[2], s2, y + y);
         float inner = fabsf(fmaf(L[4], y, L[5]));
         float outer = fabsf(fmaf(L[3], y * y, inner) + L[6]) + L[7];
-        out.ql = (L[0] * s1) * B * outer;
+        out.ql = (L[0] * sq) * B * outer;
     }
     return out;
 }
@@ -262,32 +250,35 @@ __device__ __forceinline__ QParts q_parts(float y)
 template <int KIND, int PREC>
 __device__ __forceinline__ float times_q(float g, float y, bool left)
 {
-    QParts p = q_parts<KIND>(y);
+    QParts p = q_parts<KIND>(y, left);
+    float out;
     if constexpr (PREC == FAST) {
-        return g * (left ? p.ql : p.qr);
+        out = g * (left ? p.ql : p.qr);
     } else {
         const bool direct = left || !(fabsf(p.small) < 0.25f);
         float base  = left ? p.ql : (direct ? p.qr : 1.0f);
         float delta = direct ? 0.0f : p.small;
-        return fmaf(g, base, g * delta);
+        out = fmaf(g, base, g * delta);
     }
+    return nan_through(y, out);
 }
 
 // (a * b) * q  (gated backward: a = grad_h, b = up)
 template <int KIND, int PREC>
 __device__ __forceinline__ float times_q(float a, float b, float y, bool left)
 {
-    QParts p = q_parts<KIND>(y);
-    float g = a * b;
+    QParts p = q_parts<KIND>(y, left);
+    float g = a * b, out;
     if constexpr (PREC == FAST) {
-        return g * (left ? p.ql : p.qr);
+        out = g * (left ? p.ql : p.qr);
     } else {
         const bool direct = left || !(fabsf(p.small) < 0.25f);
         float base  = left ? p.ql : (direct ? p.qr : 1.0f);
         float delta = direct ? 0.0f : p.small;
         float e = fmaf(a, b, -g);                              // a b = g + e exactly
-        return fmaf(g, base, fmaf(g, delta, e * (base + delta)));
+        out = fmaf(g, base, fmaf(g, delta, e * (base + delta)));
     }
+    return nan_through(y, out);
 }
 
 }  // namespace invact_dev
