@@ -39,6 +39,9 @@ using namespace invact_dev;
 #ifndef INVACT_NT
 #define INVACT_NT 1
 #endif
+#ifndef INVACT_MASK_NT
+#define INVACT_MASK_NT 1
+#endif
 #ifndef INVACT_DEFAULT_BLOCKS_PER_CU
 #define INVACT_DEFAULT_BLOCKS_PER_CU 0
 #endif
@@ -56,6 +59,10 @@ template <class T> __device__ __forceinline__ T ld(const T* p)
 template <class T> __device__ __forceinline__ void st(T* p, T v)
 {
     if constexpr (kNonTemporal) __builtin_nontemporal_store(v, p); else *p = v;
+}
+__device__ __forceinline__ void st_mask(uint8_t* p, uint8_t v)
+{
+    if constexpr (kNonTemporal && INVACT_MASK_NT != 0) __builtin_nontemporal_store(v, p); else *p = v;
 }
 
 // value of the neighbouring lane (lane ^ 1); every lane of the quad must be active
@@ -109,7 +116,7 @@ template <> struct Storage<INVACT_FP32> {
         const uint32_t other = swap_with_neighbour(m);
         const uint32_t byte = (c & 1) ? (((other >> 4) & 0xFu) | (m & 0xF0u))
                                       : ((m & 0xFu) | ((other & 0xFu) << 4));
-        st(mask + mask_index(c), (uint8_t)byte);
+        st_mask(mask + mask_index(c), (uint8_t)byte);
     }
     static __device__ __forceinline__ uint32_t load_mask(const uint8_t* mask, size_t c)
     {
@@ -145,7 +152,7 @@ template <> struct Storage<INVACT_BF16> {
         st(reinterpret_cast<u32x4*>(p) + c,
            u32x4{pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7])});
     }
-    static __device__ __forceinline__ void store_mask(uint8_t* mask, size_t c, uint32_t m) { st(mask + c, (uint8_t)m); }
+    static __device__ __forceinline__ void store_mask(uint8_t* mask, size_t c, uint32_t m) { st_mask(mask + c, (uint8_t)m); }
     static __device__ __forceinline__ uint32_t load_mask(const uint8_t* mask, size_t c) { return ld(mask + c); }
     static __device__ __forceinline__ float load1(const void* p, size_t i)
     {

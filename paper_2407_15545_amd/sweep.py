@@ -41,7 +41,7 @@ def timeit(fn, iters):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--sizes", type=int, nargs="+", default=[20, 22, 24, 26, 28], help="log2 of the element counts")
+    ap.add_argument("--sizes", type=int, nargs="*", default=[20, 22, 24, 26, 28], help="log2 of the element counts")
     ap.add_argument("--elements", type=int, nargs="*", default=[], help="extra element counts (e.g. 234881024)")
     ap.add_argument("--kinds", nargs="+", default=["gelu_tanh", "gelu_erf", "silu"])
     ap.add_argument("--dtypes", nargs="+", default=["bf16", "fp32"])
