@@ -67,6 +67,10 @@ def load(path=None):
         "oracle_invact_bwd": (None, [c_int, _dbl_p, _u8_p, _dbl_p, _dbl_p, c_size]),
         "oracle_glu_fwd": (None, [c_int, c_int, _dbl_p, _dbl_p, _dbl_p, _dbl_p, _dbl_p, _u8_p, c_size]),
         "oracle_glu_bwd": (None, [c_int, _dbl_p, _dbl_p, _u8_p, _dbl_p, _dbl_p, _dbl_p, c_size]),
+        "oracle_tag_lsb": (c_dbl, [c_int, c_dbl, c_int]),
+        "oracle_read_lsb": (c_int, [c_int, c_dbl]),
+        "oracle_pbit_fwd": (None, [c_int, c_int, _dbl_p, _dbl_p, _dbl_p, c_size]),
+        "oracle_pbit_bwd": (None, [c_int, c_int, _dbl_p, _dbl_p, _dbl_p, c_size]),
         "oracle_num_threads": (c_int, []),
     }
     for name, (res, args) in protos.items():
@@ -217,6 +221,23 @@ def glu_bwd(kind, a, up, mask, grad_h):
     gg = np.empty_like(a); gu = np.empty_like(a)
     lib().oracle_glu_bwd(_kind(kind), a, up, mask, g, gg, gu, a.size)
     return gg, gu
+
+
+def pbit_fwd(kind, dtype, x):
+    """Precision-bit forward -> (y_exact, y_stored with its lowest bit set to s)"""
+    x = _f64(x)
+    ye = np.empty_like(x); ys = np.empty_like(x)
+    lib().oracle_pbit_fwd(_kind(kind), _dtype(dtype), x, ye, ys, x.size)
+    return ye, ys
+
+
+def pbit_bwd(kind, dtype, y, grad_y):
+    """Precision-bit backward -> grad_x (unrounded double); s is read from y's lowest bit"""
+    y = _f64(y); g = _f64(grad_y)
+    assert y.size == g.size
+    gx = np.empty_like(y)
+    lib().oracle_pbit_bwd(_kind(kind), _dtype(dtype), y, g, gx, y.size)
+    return gx
 
 
 def num_threads():

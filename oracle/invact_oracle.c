@@ -13,6 +13,7 @@
  *   O4  the closed-form approximation q(y, s)       Eqs. (5)-(8), Appendix "Approximation Coefficients"
  *   forward / backward of the layer                 Listing "forward-backward" (Algorithm 1)
  *   SwiGLU / GeGLU gated variants                   Experiments, "GeGLU" block; Limitations
+ *   precision-bit variant                           Method, "Precision Bit Inverted Activation" and its listing
  *
  * Pin status.  O1, O2, O3 are pinned by identities, library routines and brute
  * force (tests/test_oracle_*.py).  O4 is "parity unpinned": the paper prints
@@ -470,6 +471,57 @@ void oracle_glu_bwd(int kind, const double *a, const double *up, const uint8_t *
         grad_up[i]   = grad_h[i] * a[i];
         grad_gate[i] = grad_h[i] * up[i] * q_with(&c, kind, a[i], s);
     }
+}
+
+/* ------------------------------------------------------------------ */
+/* Precision-bit variant                                               */
+/* ------------------------------------------------------------------ */
+
+/* Position of the lowest significand bit of the storage format inside the
+ * binary32 pattern of a stored value (a bfloat16 is the upper half of one). */
+static uint32_t lsb_mask(int dtype) { return dtype == DTYPE_BF16 ? 0x00010000u : 0x00000001u; }
+
+/* Y = (Y & ~1) | S on the storage format's bit pattern. */
+double oracle_tag_lsb(int dtype, double stored, int s)
+{
+    float f = (float)stored;              /* exact: stored lies on the grid */
+    uint32_t bits;
+    memcpy(&bits, &f, sizeof bits);
+    bits = (bits & ~lsb_mask(dtype)) | (s ? lsb_mask(dtype) : 0u);
+    memcpy(&f, &bits, sizeof f);
+    return (double)f;
+}
+
+/* S = Y & 1 */
+int oracle_read_lsb(int dtype, double stored)
+{
+    float f = (float)stored;
+    uint32_t bits;
+    memcpy(&bits, &f, sizeof bits);
+    return (bits & lsb_mask(dtype)) != 0;
+}
+
+/* Forward: S = X < T; Y = f(X) rounded to the storage dtype; lowest bit of Y := S.
+ * The tagged Y is both what the layer returns and what it saves. */
+void oracle_pbit_fwd(int kind, int dtype, const double *x, double *y_exact, double *y_stored, size_t n)
+{
+    init_consts();
+    double T = T_f32[kind];
+#pragma omp parallel for schedule(static)
+    for (size_t i = 0; i < n; ++i) {
+        y_exact[i]  = oracle_f_scalar(kind, x[i]);
+        y_stored[i] = oracle_tag_lsb(dtype, oracle_round_scalar(dtype, y_exact[i]), x[i] < T);
+    }
+}
+
+/* Backward: S = Y & 1; dX = dY * q(Y, S), with Y the saved (tagged) value. */
+void oracle_pbit_bwd(int kind, int dtype, const double *y, const double *grad_y, double *grad_x, size_t n)
+{
+    init_consts();
+    coeff_set c; default_coeffs(&c);
+#pragma omp parallel for schedule(static)
+    for (size_t i = 0; i < n; ++i)
+        grad_x[i] = grad_y[i] * q_with(&c, kind, y[i], oracle_read_lsb(dtype, y[i]));
 }
 
 int oracle_num_threads(void)

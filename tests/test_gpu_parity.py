@@ -279,24 +279,37 @@ def test_mask_padding_is_rewritten_as_zero():
         assert np.array_equal(m.cpu().numpy(), O.pack(np.ones(n, np.uint8)))
 
 
-def test_other_stream_and_grid_shapes_give_identical_bits():
-    n = (1 << 22) + 13
-    xs = draw(n, 41, "bf16")
-    x = PT.to_device(xs, "bf16")
-    say("streams / grid shapes")
-    y0, m0 = B.invact_fwd("gelu_erf", x)
-    torch.cuda.synchronize()
-    s = torch.cuda.Stream()
-    with torch.cuda.stream(s):
-        y1, m1 = B.invact_fwd("gelu_erf", x)
-    s.synchronize()
-    assert torch.equal(y0.view(torch.int16), y1.view(torch.int16)) and torch.equal(m0, m1)
+def same_bits(a, b):
+    return torch.equal(a.view(torch.uint8), b.view(torch.uint8))
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_other_stream_and_grid_shapes_give_identical_bits(dtype):
+    """Every entry point on a side stream and as a persistent grid of several sizes: same bits as the default."""
+    n = (1 << 22) + 13 * 512 + 77
+    kind = "gelu_erf"
+    x, up, g = (PT.to_device(draw(n, 41 + i, dtype), dtype) for i in range(3))
+
+    def run_all():
+        y, m = B.invact_fwd(kind, x)
+        gx = B.invact_bwd(kind, y, m, g)
+        act, h, m2 = B.geglu_invact_fwd(kind, x, up)
+        gg, gu = B.geglu_invact_bwd(kind, act, up, m2, g)
+        torch.cuda.synchronize()
+        return [y, m, gx, act, h, m2, gg, gu]
+
+    say(f"streams / grid shapes {dtype}")
+    ref = run_all()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        got = run_all()
+    assert all(same_bits(a, b) for a, b in zip(ref, got))
     try:
         for bpc in (1, 3, 16, 64):
+            say(f"  persistent grid, {bpc} workgroups per compute unit")
             assert B.set_blocks_per_cu(bpc) == bpc
-            y2, m2 = B.invact_fwd("gelu_erf", x)
-            torch.cuda.synchronize()
-            assert torch.equal(y0.view(torch.int16), y2.view(torch.int16)) and torch.equal(m0, m2), bpc
+            got = run_all()
+            assert all(same_bits(a, b) for a, b in zip(ref, got)), bpc
     finally:
         B.set_blocks_per_cu(0)
 
