@@ -112,6 +112,21 @@ int swiglu_invact_bwd(int dtype, const void* act, const void* up,
                       void* grad_gate, void* grad_up, size_t n, hipStream_t stream);
 
 /*
+ * Precision-bit variant (Method, "Precision Bit Inverted Activation"): no mask
+ * tensor; the lowest significand bit of every stored y carries the indicator,
+ * so the forward's output differs from f(x) by up to one more unit in the last
+ * place.
+ *   forward:  y[i] = f(x[i]) rounded to dtype, then bit 0 of its pattern := (x[i] < T)
+ *   backward: s_i = bit 0 of y[i];  grad_x[i] = grad_y[i] * q(y[i], s_i),
+ *             q evaluated at the stored (tagged) y
+ * x, y, grad_y: in / out as named, n elements each; y == x and grad_x == grad_y
+ * may alias.
+ */
+int invact_pbit_fwd(int kind, int dtype, const void* x, void* y, size_t n, hipStream_t stream);
+int invact_pbit_bwd(int kind, int dtype, const void* y, const void* grad_y, void* grad_x,
+                    size_t n, hipStream_t stream);
+
+/*
  * Launch tuning (process-wide, for benchmarking).  By default every 256-thread
  * workgroup handles one tile and retires.  blocks_per_cu in 1..64 switches to
  * a persistent grid of that many workgroups per compute unit striding over

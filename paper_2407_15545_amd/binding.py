@@ -25,6 +25,8 @@ _PROTOTYPES = {
     "invact_bwd": (_int, [_int, _int, _vp, _vp, _vp, _vp, _sz, _vp]),
     "geglu_invact_fwd": (_int, [_int, _int, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "geglu_invact_bwd": (_int, [_int, _int, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "invact_pbit_fwd": (_int, [_int, _int, _vp, _vp, _sz, _vp]),
+    "invact_pbit_bwd": (_int, [_int, _int, _vp, _vp, _vp, _sz, _vp]),
     "swiglu_invact_fwd": (_int, [_int, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "swiglu_invact_bwd": (_int, [_int, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
 }
@@ -144,6 +146,25 @@ def geglu_invact_bwd(kind, act, up, mask, grad_h, grad_gate=None, grad_up=None, 
                                       grad_h.data_ptr(), grad_gate.data_ptr(), grad_up.data_ptr(), n,
                                       _stream(stream)))
     return grad_gate, grad_up
+
+
+def invact_pbit_fwd(kind, x, y=None, stream=None):
+    """Precision-bit forward: y = f(x) with the indicator in y's lowest bit.  Returns y."""
+    y = torch.empty_like(x) if y is None else y
+    dt, n = _tensors(x, y)
+    with torch.cuda.device(x.device):
+        _check(lib().invact_pbit_fwd(_kind(kind), dt, x.data_ptr(), y.data_ptr(), n, _stream(stream)))
+    return y
+
+
+def invact_pbit_bwd(kind, y, grad_y, grad_x=None, stream=None):
+    """Precision-bit backward: grad_x = grad_y * q(y, bit 0 of y).  Returns grad_x."""
+    grad_x = torch.empty_like(grad_y) if grad_x is None else grad_x
+    dt, n = _tensors(y, grad_y, grad_x)
+    with torch.cuda.device(y.device):
+        _check(lib().invact_pbit_bwd(_kind(kind), dt, y.data_ptr(), grad_y.data_ptr(), grad_x.data_ptr(), n,
+                                     _stream(stream)))
+    return grad_x
 
 
 def swiglu_invact_fwd(gate, up, act=None, h=None, mask=None, stream=None):

@@ -126,6 +126,28 @@ template <> struct Storage<INVACT_FP32> {
     }
     static __device__ __forceinline__ float load1(const void* p, size_t i) { return reinterpret_cast<const float*>(p)[i]; }
     static __device__ __forceinline__ void store1(void* p, size_t i, float v) { reinterpret_cast<float*>(p)[i] = v; }
+    // precision-bit variant: bit 0 of each stored pattern := bit j of m / read it back
+    static __device__ __forceinline__ float tag(float v, uint32_t bit)
+    {
+        return __uint_as_float((__float_as_uint(v) & ~1u) | bit);
+    }
+    static __device__ __forceinline__ uint32_t lsb(float v) { return __float_as_uint(v) & 1u; }
+    static __device__ __forceinline__ void store_tagged(void* p, size_t c, float (&v)[8], uint32_t m)
+    {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = tag(v[j], (m >> j) & 1u);
+        store(p, c, v);
+    }
+    static __device__ __forceinline__ uint32_t unpack_tagged(const Raw& r, float (&v)[8])
+    {
+        unpack(r, v);
+        uint32_t m = 0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) m |= lsb(v[j]) << j;
+        return m;
+    }
+    static __device__ __forceinline__ void store1_tagged(void* p, size_t i, float v, bool bit) { store1(p, i, tag(v, bit)); }
+    static __device__ __forceinline__ bool lsb1(const void* p, size_t i) { return lsb(load1(p, i)); }
 };
 
 template <> struct Storage<INVACT_BF16> {
@@ -162,10 +184,36 @@ template <> struct Storage<INVACT_BF16> {
     {
         reinterpret_cast<uint16_t*>(p)[i] = (uint16_t)(pack2(v, 0.0f) & 0xFFFFu);
     }
+    // precision-bit variant: bit 0 of each stored 16-bit pattern := bit j of m / read it back
+    static __device__ __forceinline__ void store_tagged(void* p, size_t c, float (&v)[8], uint32_t m)
+    {
+        u32x4 w;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t bits = ((m >> (2 * j)) & 1u) | (((m >> (2 * j + 1)) & 1u) << 16);
+            w[j] = (pack2(v[2 * j], v[2 * j + 1]) & 0xFFFEFFFEu) | bits;
+        }
+        st(reinterpret_cast<u32x4*>(p) + c, w);
+    }
+    static __device__ __forceinline__ uint32_t unpack_tagged(const Raw& r, float (&v)[8])
+    {
+        unpack(r, v);
+        uint32_t m = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) m |= ((r.w[j] & 1u) << (2 * j)) | (((r.w[j] >> 16) & 1u) << (2 * j + 1));
+        return m;
+    }
+    static __device__ __forceinline__ void store1_tagged(void* p, size_t i, float v, bool bit)
+    {
+        reinterpret_cast<uint16_t*>(p)[i] = (uint16_t)((pack2(v, 0.0f) & 0xFFFEu) | (uint32_t)bit);
+    }
+    static __device__ __forceinline__ bool lsb1(const void* p, size_t i) { return reinterpret_cast<const uint16_t*>(p)[i] & 1u; }
 };
 
+enum MaskMode { MASK_NONE = 0, MASK_WRITE = 1, MASK_READ = 2 };
+
 // ---------------------------------------------------------------------------
-// The four element-wise operations.  Each has
+// The element-wise operations.  Each has
 //   In      -- the raw registers of one chunk of every input stream
 //   load    -- fill In for chunk c
 //   run     -- compute and store chunk c
@@ -196,7 +244,7 @@ struct FwdOp {                       // y = f(x), s = [x < T]
         S::store1(y, i, act<KIND, S::kPrec>(v));
         return v < KindConst<KIND>::T;
     }
-    static constexpr bool kWritesMask = true;
+    static constexpr int kMask = MASK_WRITE;
 };
 
 template <int KIND, int DT>
@@ -220,7 +268,7 @@ struct BwdOp {                       // grad_x = grad_y * q(y, s)
         S::store1(gx, i, times_q<KIND, S::kPrec>(S::load1(gy, i), S::load1(y, i), bit));
         return bit;
     }
-    static constexpr bool kWritesMask = false;
+    static constexpr int kMask = MASK_READ;
 };
 
 template <int KIND, int DT>
@@ -253,7 +301,7 @@ struct GluFwdOp {                    // act = f(gate), s = [gate < T], h = f(gat
         S::store1(h, i, p);
         return v < KindConst<KIND>::T;
     }
-    static constexpr bool kWritesMask = true;
+    static constexpr int kMask = MASK_WRITE;
 };
 
 template <int KIND, int DT>
@@ -284,7 +332,57 @@ struct GluBwdOp {                    // grad_up = grad_h * act ; grad_gate = gra
         S::store1(ggate, i, times_q<KIND, S::kPrec>(g, u, a, bit));
         return bit;
     }
-    static constexpr bool kWritesMask = false;
+    static constexpr int kMask = MASK_READ;
+};
+
+// Precision-bit variant: no mask tensor, the indicator travels in bit 0 of y.
+template <int KIND, int DT>
+struct PbitFwdOp {                   // y = f(x) with bit 0 := [x < T]
+    using S = Storage<DT>;
+    const void* x; void* y;
+    struct In { typename S::Raw x; };
+    __device__ __forceinline__ void load(In& in, size_t c) const { in.x = S::load(x, c); }
+    __device__ __forceinline__ void run(const In& in, size_t c) const
+    {
+        float v[8]; S::unpack(in.x, v);
+        uint32_t m = 0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            m |= (uint32_t)(v[j] < KindConst<KIND>::T) << j;
+            v[j] = act<KIND, S::kPrec>(v[j]);
+        }
+        S::store_tagged(y, c, v, m);
+    }
+    __device__ __forceinline__ bool scalar(size_t i, bool) const
+    {
+        float v = S::load1(x, i);
+        S::store1_tagged(y, i, act<KIND, S::kPrec>(v), v < KindConst<KIND>::T);
+        return false;
+    }
+    static constexpr int kMask = MASK_NONE;
+};
+
+template <int KIND, int DT>
+struct PbitBwdOp {                   // s = bit 0 of y; grad_x = grad_y * q(y, s)
+    using S = Storage<DT>;
+    const void* y; const void* gy; void* gx;
+    struct In { typename S::Raw y, g; };
+    __device__ __forceinline__ void load(In& in, size_t c) const { in.y = S::load(y, c); in.g = S::load(gy, c); }
+    __device__ __forceinline__ void run(const In& in, size_t c) const
+    {
+        float a[8], g[8];
+        const uint32_t m = S::unpack_tagged(in.y, a);
+        S::unpack(in.g, g);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) g[j] = times_q<KIND, S::kPrec>(g[j], a[j], (m >> j) & 1u);
+        S::store(gx, c, g);
+    }
+    __device__ __forceinline__ bool scalar(size_t i, bool) const
+    {
+        S::store1(gx, i, times_q<KIND, S::kPrec>(S::load1(gy, i), S::load1(y, i), S::lsb1(y, i)));
+        return false;
+    }
+    static constexpr int kMask = MASK_NONE;
 };
 
 // ---------------------------------------------------------------------------
@@ -344,14 +442,16 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(const Op op, const siz
     if (blockIdx.x == 0 && threadIdx.x < 64) {
         for (size_t base = wave_tiles * kWaveTile; base < n; base += 64) {
             const size_t i = base + threadIdx.x;
-            if constexpr (Op::kWritesMask) {
+            if constexpr (Op::kMask == MASK_WRITE) {
                 bool bit = false;
                 if (i < n) bit = op.scalar(i, false);
                 const uint64_t word = __builtin_amdgcn_ballot_w64(bit);
                 if (threadIdx.x == 0) reinterpret_cast<uint64_t*>(op.mask)[base / 64] = word;
-            } else {
+            } else if constexpr (Op::kMask == MASK_READ) {
                 const uint64_t word = reinterpret_cast<const uint64_t*>(op.mask)[base / 64];
                 if (i < n) op.scalar(i, (word >> threadIdx.x) & 1u);
+            } else {
+                if (i < n) op.scalar(i, false);
             }
         }
     }
@@ -415,6 +515,13 @@ int check_common(int kind, int dtype, size_t n)
     if (kind != INVACT_GELU_TANH && kind != INVACT_GELU_ERF && kind != INVACT_SILU) return INVACT_ERR_KIND;
     if (dtype != INVACT_FP32 && dtype != INVACT_BF16) return INVACT_ERR_DTYPE;
     if (n > SIZE_MAX - 63) return INVACT_ERR_SIZE;
+    return INVACT_OK;
+}
+
+int check_data(std::initializer_list<const void*> data)
+{
+    for (const void* p : data) if (p == nullptr) return INVACT_ERR_NULL;
+    for (const void* p : data) if (!aligned(p, 16)) return INVACT_ERR_ALIGN;
     return INVACT_OK;
 }
 
@@ -495,6 +602,27 @@ int geglu_invact_bwd(int kind, int dtype, const void* act, const void* up, const
     return dispatch(kind, dtype, [&](auto K, auto D) {
         return launch(GluBwdOp<K.value, D.value>{act, up, static_cast<const uint8_t*>(mask), grad_h,
                                                  grad_gate, grad_up}, n, stream);
+    });
+}
+
+int invact_pbit_fwd(int kind, int dtype, const void* x, void* y, size_t n, hipStream_t stream)
+{
+    if (int e = check_common(kind, dtype, n)) return e;
+    if (n == 0) return INVACT_OK;
+    if (int e = check_data({x, y})) return e;
+    return dispatch(kind, dtype, [&](auto K, auto D) {
+        return launch(PbitFwdOp<K.value, D.value>{x, y}, n, stream);
+    });
+}
+
+int invact_pbit_bwd(int kind, int dtype, const void* y, const void* grad_y, void* grad_x, size_t n,
+                    hipStream_t stream)
+{
+    if (int e = check_common(kind, dtype, n)) return e;
+    if (n == 0) return INVACT_OK;
+    if (int e = check_data({y, grad_y, grad_x})) return e;
+    return dispatch(kind, dtype, [&](auto K, auto D) {
+        return launch(PbitBwdOp<K.value, D.value>{y, grad_y, grad_x}, n, stream);
     });
 }
 

@@ -20,6 +20,7 @@ PEAK = 8000.0
 BYTES = {  # algorithmic bytes per element: (fp32, bf16)
     "invact_fwd": (8.125, 4.125), "invact_bwd": (12.125, 6.125),
     "geglu_invact_fwd": (16.125, 8.125), "geglu_invact_bwd": (20.125, 10.125),
+    "invact_pbit_fwd": (8.0, 4.0), "invact_pbit_bwd": (12.0, 6.0),
 }
 
 
@@ -66,7 +67,10 @@ def main():
                 for kind in args.kinds:
                     B.invact_fwd(kind, a, y=o1, mask=mask)          # a valid (y, mask) pair for the backward
                     y_saved = o1.clone()
+                    y_tagged = B.invact_pbit_fwd(kind, a)
                     calls = {
+                        "invact_pbit_fwd": lambda: B.invact_pbit_fwd(kind, a, y=o1),
+                        "invact_pbit_bwd": lambda: B.invact_pbit_bwd(kind, y_tagged, b, grad_x=o1),
                         "invact_fwd": lambda: B.invact_fwd(kind, a, y=o1, mask=mask),
                         "invact_bwd": lambda: B.invact_bwd(kind, y_saved, mask, b, grad_x=o1),
                         "geglu_invact_fwd": lambda: B.geglu_invact_fwd(kind, a, b, act=o1, h=o2, mask=mask),

@@ -70,6 +70,10 @@ def test_argument_validation_happens_before_any_launch():
     assert lib.geglu_invact_bwd(0, 1, a16, a16, a16, a16, a16, None, 8, None) == ERR_NULL
     assert lib.swiglu_invact_fwd(1, a16, a16, a16, a8, a16, 8, None) == ERR_ALIGN
     assert lib.swiglu_invact_bwd(7, a16, a16, a16, a16, a16, a16, 8, None) == ERR_DTYPE
+    assert lib.invact_pbit_fwd(0, 0, a16, None, 8, None) == ERR_NULL
+    assert lib.invact_pbit_fwd(0, 1, a8, a16, 8, None) == ERR_ALIGN
+    assert lib.invact_pbit_bwd(3, 1, a16, a16, a16, 8, None) == ERR_KIND
+    assert lib.invact_pbit_bwd(0, 1, a16, a16, a16, 0, None) == OK
     # n == 0 is a successful no-op, whatever the pointers
     assert fwd(0, 0, None, None, None, 0, None) == OK
     assert bwd(2, 1, None, None, None, None, 0, None) == OK
