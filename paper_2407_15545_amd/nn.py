@@ -1,0 +1,127 @@
+"""Drop-in PyTorch layers over libinvact (Introduction, Listing 1; Algorithm 1).
+
+    for layer in model.layers:
+        layer.act_fn = InvActGELU()
+
+Each layer's autograd function calls the C ABI for both passes and saves the
+layer's OUTPUT plus the packed 1-bit mask instead of its input.  The output is
+the tensor the next layer saves anyway, so between the two layers one tensor is
+kept instead of two.  There is no CPU or eager fallback: tensors must live on
+the GPU and be float32 or bfloat16.
+"""
+import torch
+
+from . import binding as B
+
+
+class _InvAct(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, x, kind):
+        y, mask = B.invact_fwd(kind, x.contiguous())
+        ctx.kind = kind
+        ctx.save_for_backward(y, mask)
+        return y.view_as(x)
+
+    @staticmethod
+    def backward(ctx, grad_y):
+        y, mask = ctx.saved_tensors
+        return B.invact_bwd(ctx.kind, y, mask, grad_y.contiguous()).view_as(grad_y), None
+
+
+class _InvActPrecisionBit(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, x, kind):
+        y = B.invact_pbit_fwd(kind, x.contiguous())
+        ctx.kind = kind
+        ctx.save_for_backward(y)
+        return y.view_as(x)
+
+    @staticmethod
+    def backward(ctx, grad_y):
+        (y,) = ctx.saved_tensors
+        return B.invact_pbit_bwd(ctx.kind, y, grad_y.contiguous()).view_as(grad_y), None
+
+
+class _InvActGLU(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, gate, up, kind):
+        up = up.contiguous()
+        act, h, mask = B.geglu_invact_fwd(kind, gate.contiguous(), up)
+        ctx.kind = kind
+        ctx.save_for_backward(act, up, mask)
+        return h.view_as(gate)
+
+    @staticmethod
+    def backward(ctx, grad_h):
+        act, up, mask = ctx.saved_tensors
+        grad_gate, grad_up = B.geglu_invact_bwd(ctx.kind, act, up, mask, grad_h.contiguous())
+        return grad_gate.view_as(grad_h), grad_up.view_as(grad_h), None
+
+
+def invact(x, kind="gelu_erf", precision_bit=False):
+    """y = f(x) with the inverted-activation backward."""
+    return (_InvActPrecisionBit if precision_bit else _InvAct).apply(x, kind)
+
+
+def invact_glu(gate, up, kind="silu"):
+    """h = f(gate) * up with the inverted-activation backward (SwiGLU for kind='silu', GeGLU for the GELUs)."""
+    return _InvActGLU.apply(gate, up, kind)
+
+
+class InvAct(torch.nn.Module):
+    def __init__(self, kind, precision_bit=False):
+        super().__init__()
+        if kind not in B.KINDS:
+            raise ValueError(f"kind must be one of {sorted(B.KINDS)}")
+        self.kind, self.precision_bit = kind, precision_bit
+
+    def forward(self, x):
+        return invact(x, self.kind, self.precision_bit)
+
+    def extra_repr(self):
+        return f"kind={self.kind!r}, precision_bit={self.precision_bit}"
+
+
+class InvActGELU(InvAct):
+    """Replacement for torch.nn.GELU (approximate='none' or 'tanh')."""
+
+    def __init__(self, approximate="none", precision_bit=False):
+        if approximate not in ("none", "tanh"):
+            raise ValueError("approximate must be 'none' or 'tanh'")
+        super().__init__("gelu_tanh" if approximate == "tanh" else "gelu_erf", precision_bit)
+
+
+class InvActSiLU(InvAct):
+    """Replacement for torch.nn.SiLU."""
+
+    def __init__(self, precision_bit=False):
+        super().__init__("silu", precision_bit)
+
+
+class InvActGLU(torch.nn.Module):
+    """h = f(gate) * up as one fused layer (SwiGLU: kind='silu'; GeGLU: 'gelu_erf' / 'gelu_tanh')."""
+
+    def __init__(self, kind="silu"):
+        super().__init__()
+        if kind not in B.KINDS:
+            raise ValueError(f"kind must be one of {sorted(B.KINDS)}")
+        self.kind = kind
+
+    def forward(self, gate, up):
+        return invact_glu(gate, up, self.kind)
+
+
+def saved_activation_bytes(fn):
+    """Bytes of distinct tensors autograd saves while running fn() (the paper's memory metric:
+    stored activations only, parameters excluded by the caller passing them as leaves that
+    require grad -- they are saved too but are the same in both variants)."""
+    seen = {}
+
+    def pack(t):
+        if t.device.type == "cuda":
+            seen[(t.untyped_storage().data_ptr(), t.storage_offset(), tuple(t.shape))] = t.numel() * t.element_size()
+        return t
+
+    with torch.autograd.graph.saved_tensors_hooks(pack, lambda t: t):
+        out = fn()
+    return sum(seen.values()), out

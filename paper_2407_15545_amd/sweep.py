@@ -52,6 +52,11 @@ def main():
     args = ap.parse_args()
     torch.cuda.set_device(0)
     sizes = [1 << s for s in args.sizes] + list(args.elements)
+    warm = torch.empty(1 << 28, device="cuda", dtype=torch.bfloat16)      # bring the clocks up before timing
+    for _ in range(300):
+        B.invact_pbit_fwd("silu", warm, y=warm)
+    torch.cuda.synchronize()
+    del warm
     for lib in args.lib:
         if lib is not None:
             B._lib, B._LIB_PATH = None, os.path.abspath(lib)

@@ -11,6 +11,9 @@ Tolerances (the reasons are derived in DESIGN.md, "Tolerances"):
              keep a result-relative bound.
   masks    : bit-exact, padding included.
 """
+import os
+import sys
+
 import numpy as np
 import torch
 
@@ -21,6 +24,17 @@ TORCH_DTYPE = {"fp32": torch.float32, "bf16": torch.bfloat16}
 F32_MAX = float(np.finfo(np.float32).max)
 BF16_MAX = float.fromhex("0x1.fep127")
 MAX_FINITE = {"fp32": F32_MAX, "bf16": BF16_MAX}
+
+
+REPORT_DIR = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+
+
+def say(*a):
+    """Name the case before a GPU step (stderr, flushed) and keep a copy where GPU runs leave their files."""
+    print(*a, file=sys.stderr, flush=True)
+    if os.path.isdir(REPORT_DIR):
+        with open(os.path.join(REPORT_DIR, "parity_report.txt"), "a") as fh:
+            print(*a, file=fh)
 
 
 def ulp(ref, dtype):

@@ -1,0 +1,89 @@
+"""The PyTorch layers over the C ABI: gradients against torch's own autograd (up to the
+approximation error of q, which the paper only plots), and the saved-activation memory
+the method exists for (Introduction; Appendix "Memory Table")."""
+import pytest
+import torch
+import torch.nn.functional as F
+
+import parity as PT
+from paper_2407_15545_amd import nn as inv
+
+pytestmark = pytest.mark.gpu
+
+
+REFS = {"gelu_erf": lambda x: F.gelu(x), "gelu_tanh": lambda x: F.gelu(x, approximate="tanh"), "silu": F.silu}
+
+
+@pytest.mark.parametrize("precision_bit", [False, True])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("kind", ["gelu_erf", "gelu_tanh", "silu"])
+def test_layer_matches_torch_autograd(kind, dtype, precision_bit):
+    torch.manual_seed(0)
+    x = (torch.randn(64, 1000, device="cuda") * 2).to(dtype).requires_grad_()
+    g = torch.randn(64, 1000, device="cuda").to(dtype)
+    PT.say(f"nn layer {kind} {dtype} precision_bit={precision_bit}")
+    y = inv.invact(x, kind, precision_bit)
+    (gx,) = torch.autograd.grad(y, x, g)
+    xr = x.detach().double().requires_grad_()
+    yr = REFS[kind](xr)
+    (gr,) = torch.autograd.grad(yr, xr, g.double())
+    # wiring check only (ulp-level parity with the oracle is in test_gpu_parity.py / test_gpu_pbit.py)
+    eps = 2.0 ** -6 if dtype == torch.bfloat16 else 1e-5
+    assert torch.all((y.double() - yr).abs() <= eps * yr.abs() + 1e-9)
+    # q approximates f'(x) to a few 1e-2 at worst (GELU just right of the minimum)
+    assert torch.all((gx.double() - gr).abs() <= (4e-2 + 4 * eps) * g.double().abs() + 1e-9)
+
+
+@pytest.mark.parametrize("kind", ["silu", "gelu_erf"])
+def test_glu_layer_matches_torch_autograd(kind):
+    torch.manual_seed(1)
+    gate = torch.randn(32, 512, device="cuda", dtype=torch.bfloat16).requires_grad_()
+    up = torch.randn(32, 512, device="cuda", dtype=torch.bfloat16).requires_grad_()
+    gh = torch.randn(32, 512, device="cuda", dtype=torch.bfloat16)
+    PT.say(f"nn glu {kind}")
+    h = inv.InvActGLU(kind)(gate, up)
+    gg, gu = torch.autograd.grad(h, (gate, up), gh)
+    g64, u64 = gate.detach().double().requires_grad_(), up.detach().double().requires_grad_()
+    hr = REFS[kind](g64) * u64
+    ggr, gur = torch.autograd.grad(hr, (g64, u64), gh.double())
+    assert torch.all((h.double() - hr).abs() <= 2.0 ** -6 * hr.abs() + 1e-9)
+    assert torch.all((gu.double() - gur).abs() <= 2.0 ** -5 * gur.abs() + 1e-9)
+    assert torch.all((gg.double() - ggr).abs() <= 5e-2 * (gh.double() * u64).abs() + 1e-9)
+
+
+def test_saved_activation_memory_of_a_transformer_mlp_stack():
+    """Linear -> act -> Linear blocks (BERT-base MLP shape), bf16: the standard layer keeps the
+    activation's input AND output, the inverted one keeps the output and 1/16 of a tensor."""
+    torch.manual_seed(2)
+    layers, d, tokens = 4, 768, 2048
+    w1 = [torch.randn(4 * d, d, device="cuda", dtype=torch.bfloat16, requires_grad=True) for _ in range(layers)]
+    w2 = [torch.randn(d, 4 * d, device="cuda", dtype=torch.bfloat16, requires_grad=True) for _ in range(layers)]
+    x0 = torch.randn(tokens, d, device="cuda", dtype=torch.bfloat16, requires_grad=True)
+
+    def run(act):
+        def fn():
+            x = x0
+            for a, b in zip(w1, w2):
+                x = x + F.linear(act(F.linear(x, a)), b) * 0.01
+            return x
+        return inv.saved_activation_bytes(fn)[0]
+
+    PT.say("saved-activation memory")
+    weights = sum(w.numel() * 2 for w in w1 + w2)
+    base = run(F.gelu) - weights
+    ours = run(inv.InvActGELU()) - weights
+    pbit = run(inv.InvActGELU(precision_bit=True)) - weights
+    # per block: x (d) + pre-activation (4d) + activation (4d) -> x + activation + mask (4d/16)
+    per_token = tokens * 2
+    assert base == layers * per_token * (d + 4 * d + 4 * d)
+    assert ours == layers * (per_token * (d + 4 * d) + tokens * 4 * d // 8)
+    assert pbit == layers * per_token * (d + 4 * d)
+    saving = 1 - ours / base
+    PT.say(f"  saved activations: torch {base / 1e6:.1f} MB, InvAct {ours / 1e6:.1f} MB ({-100 * saving:.1f} %), "
+        f"precision-bit {pbit / 1e6:.1f} MB ({-100 * (1 - pbit / base):.1f} %)")
+    assert 0.40 < saving < 0.45
+
+
+def test_layers_refuse_cpu_tensors():
+    with pytest.raises((ValueError, RuntimeError)):
+        inv.InvActSiLU()(torch.randn(8))

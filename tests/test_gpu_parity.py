@@ -5,9 +5,6 @@ Sizes here are ones the oracle finishes in seconds; they span many 8-element
 chunks, several workgroups and ragged tails.  Full-size workloads are in
 test_gpu_workloads.py.
 """
-import os
-import sys
-
 import numpy as np
 import pytest
 import torch
@@ -18,19 +15,10 @@ from paper_2407_15545_amd import binding as B
 from paper_2407_15545_amd import synth
 
 pytestmark = pytest.mark.gpu
-REPORT_DIR = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
 
 KINDS = ["gelu_tanh", "gelu_erf", "silu"]
 DTYPES = ["fp32", "bf16"]
 SIZES = [1, 7, 8, 63, 64, 65, 511, 513, 4096 + 8, (1 << 20) + 3]
-
-
-def say(*a):
-    """Name the case before the GPU step (stderr, flushed); keep a copy where GPU runs leave their files."""
-    print(*a, file=sys.stderr, flush=True)
-    if os.path.isdir(REPORT_DIR):
-        with open(os.path.join(REPORT_DIR, "parity_report.txt"), "a") as fh:
-            print(*a, file=fh)
 
 
 def draw(n, seed, dtype, std=2.0):
@@ -47,7 +35,7 @@ def mask_of(t):
 @pytest.mark.parametrize("kind", KINDS)
 def test_fwd_matches_oracle(kind, dtype):
     for n in SIZES:
-        say(f"invact_fwd {kind} {dtype} n={n}")
+        PT.say(f"invact_fwd {kind} {dtype} n={n}")
         xs = draw(n, n, dtype)
         x64 = synth.storage_to_f64(xs, dtype)
         ye, _, m_ref = O.invact_fwd(kind, dtype, x64)
@@ -68,7 +56,7 @@ def test_fwd_every_bf16_input(kind, dtype):
     with np.errstate(invalid="ignore"):
         x64 = synth.storage_to_f64(xs, dtype)
     ye, _, m_ref = O.invact_fwd(kind, dtype, x64)
-    say(f"invact_fwd {kind} {dtype} all bf16 patterns")
+    PT.say(f"invact_fwd {kind} {dtype} all bf16 patterns")
     y, m = B.invact_fwd(kind, PT.to_device(xs, dtype))
     torch.cuda.synchronize()
     assert np.array_equal(mask_of(m), m_ref)
@@ -90,7 +78,7 @@ def test_fwd_fp32_dense_ranges(kind):
     xs = np.concatenate(parts).astype(np.float32)
     x64 = xs.astype(np.float64)
     ye, _, m_ref = O.invact_fwd(kind, "fp32", x64)
-    say(f"invact_fwd {kind} fp32 dense ranges n={xs.size}")
+    PT.say(f"invact_fwd {kind} fp32 dense ranges n={xs.size}")
     y, m = B.invact_fwd(kind, PT.to_device(xs, "fp32"))
     torch.cuda.synchronize()
     assert np.array_equal(mask_of(m), m_ref)
@@ -113,7 +101,7 @@ def bwd_case(kind, dtype, n, seed):
 @pytest.mark.parametrize("kind", KINDS)
 def test_bwd_matches_oracle(kind, dtype):
     for n in SIZES:
-        say(f"invact_bwd {kind} {dtype} n={n}")
+        PT.say(f"invact_bwd {kind} {dtype} n={n}")
         ys64, m_ref, gs, g64 = bwd_case(kind, dtype, n, 100 + n)
         ref = O.invact_bwd(kind, ys64, m_ref, g64)
         y_dev = PT.to_device(synth.f64_to_storage_exact(ys64, dtype), dtype)
@@ -139,7 +127,7 @@ def test_bwd_every_bf16_y_and_both_mask_bits(kind):
     m = O.pack(s)
     g = np.ones(bits.size)
     ref = O.invact_bwd(kind, y64, m, g)
-    say(f"invact_bwd {kind} bf16 all (y, s) pairs")
+    PT.say(f"invact_bwd {kind} bf16 all (y, s) pairs")
     gx = B.invact_bwd(kind, PT.to_device(bits, "bf16"), torch.from_numpy(m).cuda(),
                       PT.to_device(synth.to_storage(g.astype(np.float32), "bf16"), "bf16"))
     torch.cuda.synchronize()
@@ -167,7 +155,7 @@ def test_bwd_fp32_dense_in_y(kind):
     g = rng.standard_normal(y.size).astype(np.float32)
     m = O.pack(s)
     ref = O.invact_bwd(kind, y.astype(np.float64), m, g.astype(np.float64))
-    say(f"invact_bwd {kind} fp32 dense y n={y.size}")
+    PT.say(f"invact_bwd {kind} fp32 dense y n={y.size}")
     gx = B.invact_bwd(kind, PT.to_device(y, "fp32"), torch.from_numpy(m).cuda(), PT.to_device(g, "fp32"))
     torch.cuda.synchronize()
     got = PT.to_f64(gx)
@@ -178,7 +166,7 @@ def test_bwd_fp32_dense_in_y(kind):
     fin = np.isfinite(lit)
     absq = np.abs(got - ref)[fin] / np.abs(g)[fin]
     small = np.abs(ref[fin] / g[fin]) < 0.5
-    say(f"  {kind}: max |gpu-ref|/|g| = {absq.max():.3g} (where |q| < 0.5: {absq[small].max():.3g}), "
+    PT.say(f"  {kind}: max |gpu-ref|/|g| = {absq.max():.3g} (where |q| < 0.5: {absq[small].max():.3g}), "
         f"literal max ulp = {lit[fin].max():.3g}, share over 2 ulp = {(lit[fin] > 2).mean():.3g}")
 
 
@@ -188,7 +176,7 @@ def test_bwd_fp32_dense_in_y(kind):
 @pytest.mark.parametrize("kind", KINDS)
 def test_gated_fwd_bwd_match_oracle(kind, dtype):
     for n in SIZES:
-        say(f"geglu fwd/bwd {kind} {dtype} n={n}")
+        PT.say(f"geglu fwd/bwd {kind} {dtype} n={n}")
         gate_s, up_s, gh_s = draw(n, 200 + n, dtype, 1.5), draw(n, 201 + n, dtype, 1.0), draw(n, 202 + n, dtype, 0.01)
         gate, up, gh = (synth.storage_to_f64(a, dtype) for a in (gate_s, up_s, gh_s))
         ae, as_, he, m_ref = O.glu_fwd(kind, dtype, gate, up)
@@ -215,7 +203,7 @@ def test_swiglu_entry_points_equal_geglu_with_silu():
     n = 70001
     gate_s, up_s, gh_s = draw(n, 5, "bf16"), draw(n, 6, "bf16", 1.0), draw(n, 7, "bf16", 0.01)
     gate, up, gh = (PT.to_device(a, "bf16") for a in (gate_s, up_s, gh_s))
-    say("swiglu_invact_fwd/bwd vs geglu(silu)")
+    PT.say("swiglu_invact_fwd/bwd vs geglu(silu)")
     a1, h1, m1 = B.swiglu_invact_fwd(gate, up)
     a2, h2, m2 = B.geglu_invact_fwd("silu", gate, up)
     g1 = B.swiglu_invact_bwd(a1, up, m1, gh)
@@ -237,7 +225,7 @@ def test_in_place_and_canaries(dtype):
     gs = draw(n, 32, dtype, 1.0)
     x = PT.to_device(xs, dtype)
     td = PT.TORCH_DTYPE[dtype]
-    say(f"in-place / canaries {dtype}")
+    PT.say(f"in-place / canaries {dtype}")
     # reference results out of place
     y_ref, m_ref = B.invact_fwd(kind, x)
     gx_ref = B.invact_bwd(kind, y_ref, m_ref, PT.to_device(gs, dtype))
@@ -273,7 +261,7 @@ def test_mask_padding_is_rewritten_as_zero():
     for n in (1, 9, 65, 127, 129, 1000):
         m = torch.full((B.mask_bytes(n),), 0xFF, dtype=torch.uint8, device="cuda")
         x = torch.full((n,), -5.0, dtype=torch.bfloat16, device="cuda")      # every bit set
-        say(f"mask padding n={n}")
+        PT.say(f"mask padding n={n}")
         B.invact_fwd("silu", x, mask=m)
         torch.cuda.synchronize()
         assert np.array_equal(m.cpu().numpy(), O.pack(np.ones(n, np.uint8)))
@@ -298,7 +286,7 @@ def test_other_stream_and_grid_shapes_give_identical_bits(dtype):
         torch.cuda.synchronize()
         return [y, m, gx, act, h, m2, gg, gu]
 
-    say(f"streams / grid shapes {dtype}")
+    PT.say(f"streams / grid shapes {dtype}")
     ref = run_all()
     side = torch.cuda.Stream()
     with torch.cuda.stream(side):
@@ -306,7 +294,7 @@ def test_other_stream_and_grid_shapes_give_identical_bits(dtype):
     assert all(same_bits(a, b) for a, b in zip(ref, got))
     try:
         for bpc in (1, 3, 16, 64):
-            say(f"  persistent grid, {bpc} workgroups per compute unit")
+            PT.say(f"  persistent grid, {bpc} workgroups per compute unit")
             assert B.set_blocks_per_cu(bpc) == bpc
             got = run_all()
             assert all(same_bits(a, b) for a, b in zip(ref, got)), bpc
@@ -322,7 +310,7 @@ def test_nan_and_infinities_flow_through():
         x64 = np.array(special, dtype=np.float64)
         g = torch.ones_like(x)
         for kind in KINDS:
-            say(f"specials {kind} {dtype}")
+            PT.say(f"specials {kind} {dtype}")
             ye, ys, mr = O.invact_fwd(kind, dtype, x64)
             y, m = B.invact_fwd(kind, x)
             # backward from what the oracle's forward saved

@@ -5,8 +5,6 @@ Forward: bit 0 of every stored pattern must equal the indicator exactly; the
 stored value may differ from the oracle's (correctly rounded, then tagged) one
 by at most 2 ulp, i.e. one step of the even-spaced grid the tagged values live
 on.  Backward: fed with the ORACLE's stored y, same tolerance as invact_bwd."""
-import sys
-
 import numpy as np
 import pytest
 import torch
@@ -20,10 +18,6 @@ pytestmark = pytest.mark.gpu
 KINDS = ["gelu_tanh", "gelu_erf", "silu"]
 DTYPES = ["fp32", "bf16"]
 SIZES = [1, 7, 63, 64, 65, 511, 513, 4096 + 8, (1 << 20) + 3]
-
-
-def say(*a):
-    print(*a, file=sys.stderr, flush=True)
 
 
 def patterns(t):
@@ -42,7 +36,7 @@ def inputs(n, seed, dtype):
 @pytest.mark.parametrize("kind", KINDS)
 def test_pbit_forward_and_backward(kind, dtype):
     for n in SIZES:
-        say(f"invact_pbit fwd/bwd {kind} {dtype} n={n}")
+        PT.say(f"invact_pbit fwd/bwd {kind} {dtype} n={n}")
         xs, gs = inputs(n, 300 + n, dtype)
         x64, g64 = synth.storage_to_f64(xs, dtype), synth.storage_to_f64(gs, dtype)
         ye, ys = O.pbit_fwd(kind, dtype, x64)
@@ -67,7 +61,7 @@ def test_pbit_every_bf16_input(kind):
     with np.errstate(invalid="ignore"):
         x64 = synth.storage_to_f64(bits, "bf16")
     ye, ys = O.pbit_fwd(kind, "bf16", x64)
-    say(f"invact_pbit_fwd {kind} all bf16 patterns")
+    PT.say(f"invact_pbit_fwd {kind} all bf16 patterns")
     y = B.invact_pbit_fwd(kind, PT.to_device(bits, "bf16"))
     torch.cuda.synchronize()
     ok = ~np.isnan(x64)
@@ -91,7 +85,7 @@ def test_pbit_in_place(dtype):
     n = 70001
     xs, gs = inputs(n, 77, dtype)
     x, g = PT.to_device(xs, dtype), PT.to_device(gs, dtype)
-    say(f"invact_pbit in place {dtype}")
+    PT.say(f"invact_pbit in place {dtype}")
     y = B.invact_pbit_fwd("silu", x)
     gx = B.invact_pbit_bwd("silu", y, g)
     x2, g2 = x.clone(), g.clone()

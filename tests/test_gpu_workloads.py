@@ -10,7 +10,6 @@ gpurun_out/accuracy_report.json.
 """
 import json
 import os
-import sys
 
 import numpy as np
 import pytest
@@ -24,10 +23,6 @@ from paper_2407_15545_amd import synth
 pytestmark = pytest.mark.gpu
 REPORT_DIR = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
 CHUNK = 1 << 25          # oracle block (a multiple of 64, so mask words do not straddle blocks)
-
-
-def say(*a):
-    print(*a, file=sys.stderr, flush=True)
 
 
 def report(key, value):
@@ -70,10 +65,10 @@ def run_plain(name, kind, dtype, w):
     x_st, g_st = w["x"], w["grad_y"]
     idx = sample_positions(n)
     it = torch.from_numpy(idx).cuda()
-    say(f"{name}: {kind} {dtype} n={n}: oracle forward")
+    PT.say(f"{name}: {kind} {dtype} n={n}: oracle forward")
     ys_st, m_ref = oracle_forward_full(kind, dtype, x_st)
 
-    say(f"{name}: invact_fwd")
+    PT.say(f"{name}: invact_fwd")
     y, m = B.invact_fwd(kind, PT.to_device(x_st, dtype))
     torch.cuda.synchronize()
     assert np.array_equal(m.cpu().numpy(), m_ref), "mask differs"
@@ -83,7 +78,7 @@ def run_plain(name, kind, dtype, w):
     assert e.max() <= 1.0, PT.worst(e, x64, ye, PT.to_f64(y[it]))
     del y
 
-    say(f"{name}: invact_bwd")
+    PT.say(f"{name}: invact_bwd")
     gx = B.invact_bwd(kind, PT.to_device(ys_st, dtype), torch.from_numpy(m_ref).cuda(), PT.to_device(g_st, dtype))
     torch.cuda.synchronize()
     ys64 = synth.storage_to_f64(ys_st[idx], dtype)
@@ -138,10 +133,10 @@ def test_workload_swiglu_bf16_headline():
     n = w["n"]
     idx = sample_positions(n)
     it = torch.from_numpy(idx).cuda()
-    say(f"{name}: oracle forward n={n}")
+    PT.say(f"{name}: oracle forward n={n}")
     as_st, m_ref = oracle_forward_full(kind, dtype, w["gate"])
 
-    say(f"{name}: swiglu_invact_fwd")
+    PT.say(f"{name}: swiglu_invact_fwd")
     act, h, m = B.swiglu_invact_fwd(PT.to_device(w["gate"], dtype), PT.to_device(w["up"], dtype))
     torch.cuda.synchronize()
     assert np.array_equal(m.cpu().numpy(), m_ref), "mask differs"
@@ -155,7 +150,7 @@ def test_workload_swiglu_bf16_headline():
     assert np.array_equal(act[it].view(torch.int16).cpu().numpy().view(np.uint16), as_st[idx])
     del act, h
 
-    say(f"{name}: swiglu_invact_bwd")
+    PT.say(f"{name}: swiglu_invact_bwd")
     gg, gu = B.swiglu_invact_bwd(PT.to_device(as_st, dtype), PT.to_device(w["up"], dtype),
                                  torch.from_numpy(m_ref).cuda(), PT.to_device(w["grad_h"], dtype))
     torch.cuda.synchronize()
