@@ -14,11 +14,11 @@
 //             different mask bytes; neighbouring lanes swap nibbles with one
 //             DPP move so that every lane again stores (or loads) one byte.
 // The canonical little-endian bit stream thus comes out of lane-local shifts.
-// Each lane keeps kUnroll chunks in flight: all loads of a step are issued
+// Each lane keeps Op::kUnroll chunks in flight: all loads of a step are issued
 // before the first store, which is also what makes element-wise in-place use
 // (y == x and the like) safe.  By default a workgroup handles one tile of
-// kUnroll * 256 chunks and retires; every global access is non-temporal (each
-// byte is touched once).  The up to 511 elements past the last full wave tile
+// Op::kUnroll * 256 chunks and retires; the tensor accesses are non-temporal
+// (each byte is touched once).  The up to 511 elements past the last full wave tile
 // are handled one element per lane by the first wavefront, the mask word being
 // formed by a wave64 ballot there (and zero padding coming for free).
 #include <hip/hip_runtime.h>
@@ -33,14 +33,24 @@ namespace {
 
 using namespace invact_dev;
 
-#ifndef INVACT_UNROLL
-#define INVACT_UNROLL 2
+// chunks in flight per lane, per kind of operation (measured optimum on MI355X)
+#ifndef INVACT_UNROLL_FWD
+#define INVACT_UNROLL_FWD 2
+#endif
+#ifndef INVACT_UNROLL_BWD
+#define INVACT_UNROLL_BWD 2
+#endif
+#ifndef INVACT_UNROLL_GLU_FWD
+#define INVACT_UNROLL_GLU_FWD 2
+#endif
+#ifndef INVACT_UNROLL_GLU_BWD
+#define INVACT_UNROLL_GLU_BWD 2
 #endif
 #ifndef INVACT_NT
 #define INVACT_NT 1
 #endif
 #ifndef INVACT_MASK_NT
-#define INVACT_MASK_NT 1
+#define INVACT_MASK_NT 0
 #endif
 #ifndef INVACT_DEFAULT_BLOCKS_PER_CU
 #define INVACT_DEFAULT_BLOCKS_PER_CU 0
@@ -48,7 +58,6 @@ using namespace invact_dev;
 
 constexpr int  kThreads = 256;
 constexpr int  kWaveTile = 512;                   // elements per wavefront and step
-constexpr int  kUnroll  = INVACT_UNROLL;          // chunks in flight per lane
 constexpr bool kNonTemporal = INVACT_NT != 0;     // every byte is touched once: keep it out of the caches
 constexpr int  kDefaultBlocksPerCu = INVACT_DEFAULT_BLOCKS_PER_CU;   // 0: one tile per workgroup
 
@@ -245,6 +254,7 @@ struct FwdOp {                       // y = f(x), s = [x < T]
         return v < KindConst<KIND>::T;
     }
     static constexpr int kMask = MASK_WRITE;
+    static constexpr int kUnroll = INVACT_UNROLL_FWD;
 };
 
 template <int KIND, int DT>
@@ -269,6 +279,7 @@ struct BwdOp {                       // grad_x = grad_y * q(y, s)
         return bit;
     }
     static constexpr int kMask = MASK_READ;
+    static constexpr int kUnroll = INVACT_UNROLL_BWD;
 };
 
 template <int KIND, int DT>
@@ -302,6 +313,7 @@ struct GluFwdOp {                    // act = f(gate), s = [gate < T], h = f(gat
         return v < KindConst<KIND>::T;
     }
     static constexpr int kMask = MASK_WRITE;
+    static constexpr int kUnroll = INVACT_UNROLL_GLU_FWD;
 };
 
 template <int KIND, int DT>
@@ -333,6 +345,7 @@ struct GluBwdOp {                    // grad_up = grad_h * act ; grad_gate = gra
         return bit;
     }
     static constexpr int kMask = MASK_READ;
+    static constexpr int kUnroll = INVACT_UNROLL_GLU_BWD;
 };
 
 // Precision-bit variant: no mask tensor, the indicator travels in bit 0 of y.
@@ -360,6 +373,7 @@ struct PbitFwdOp {                   // y = f(x) with bit 0 := [x < T]
         return false;
     }
     static constexpr int kMask = MASK_NONE;
+    static constexpr int kUnroll = INVACT_UNROLL_FWD;
 };
 
 template <int KIND, int DT>
@@ -383,6 +397,7 @@ struct PbitBwdOp {                   // s = bit 0 of y; grad_x = grad_y * q(y, s
         return false;
     }
     static constexpr int kMask = MASK_NONE;
+    static constexpr int kUnroll = INVACT_UNROLL_BWD;
 };
 
 // ---------------------------------------------------------------------------
@@ -398,6 +413,7 @@ struct PbitBwdOp {                   // s = bit 0 of y; grad_x = grad_y * q(y, s
 template <class Op, bool PERSISTENT>
 __global__ __launch_bounds__(kThreads) void stream_kernel(const Op op, const size_t n)
 {
+    constexpr int kUnroll = Op::kUnroll;
     const size_t wave_tiles = n / kWaveTile;
     const size_t chunks = wave_tiles * 64;
 
@@ -481,6 +497,7 @@ bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) &
 template <class Op>
 int launch(const Op& op, size_t n, hipStream_t stream)
 {
+    constexpr int kUnroll = Op::kUnroll;
     const size_t chunks = (n / kWaveTile) * 64;
     const int per_cu = g_blocks_per_cu.load(std::memory_order_relaxed);
     if (per_cu == 0) {
