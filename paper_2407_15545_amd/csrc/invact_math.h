@@ -192,7 +192,7 @@ __device__ __forceinline__ float cubic_exp2(const float (&t)[4], float yt)
 // meet that 0.
 struct QParts { float ql, qr, small; };
 
-template <int KIND>
+template <int KIND, int PREC>
 __device__ __forceinline__ QParts q_parts(float y, bool left)
 {
     constexpr float fT = KindConst<KIND>::fT;
@@ -222,9 +222,17 @@ __device__ __forceinline__ QParts q_parts(float y, bool left)
         float sq  = hw_sqrt(arg);
         // Eq. (6): 1 + (c0 + c1 sqrt(yt) + c2 yt) E, with yt = arg
         float E = cubic_exp2(cst::gelu_right_exp2, arg);
-        float r = fmaf(R[2], arg, R[1] * sq);
-        out.qr    = fmaf(r, E, fmaf(R[0], E, 1.0f));
-        out.small = fmaf(r, E, R[0] * E);
+        if constexpr (PREC == FAST) {
+            float r = fmaf(R[2], arg, R[1] * sq);
+            out.qr    = fmaf(r, E, fmaf(R[0], E, 1.0f));
+            out.small = 0.0f;                                   // not used
+        } else {
+            // the same sum with E multiplied in first: the partial sums stay below 1,
+            // where binary32 is twice as fine as at c1 sqrt(yt) ~ 1
+            float sE = sq * E, c2y = R[2] * arg;
+            out.qr    = fmaf(R[1], sE, fmaf(c2y, E, fmaf(R[0], E, 1.0f)));
+            out.small = fmaf(R[1], sE, fmaf(c2y, E, R[0] * E));
+        }
         // Eq. (5): c0 sqrt(y + c1) (2y + c2 sqrt(-y)) (|c3 y^2 + |c4 y + c5| + c6| + c7)
         float s2 = hw_sqrt(fmaxf(-y, 0.0f));
         float B  = fmaf(L[2], s2, y + y);
@@ -250,7 +258,7 @@ __device__ __forceinline__ QParts q_parts(float y, bool left)
 template <int KIND, int PREC>
 __device__ __forceinline__ float times_q(float g, float y, bool left)
 {
-    QParts p = q_parts<KIND>(y, left);
+    QParts p = q_parts<KIND, PREC>(y, left);
     float out;
     if constexpr (PREC == FAST) {
         out = g * (left ? p.ql : p.qr);
@@ -267,7 +275,7 @@ __device__ __forceinline__ float times_q(float g, float y, bool left)
 template <int KIND, int PREC>
 __device__ __forceinline__ float times_q(float a, float b, float y, bool left)
 {
-    QParts p = q_parts<KIND>(y, left);
+    QParts p = q_parts<KIND, PREC>(y, left);
     float g = a * b, out;
     if constexpr (PREC == FAST) {
         out = g * (left ? p.ql : p.qr);
