@@ -322,3 +322,38 @@ def test_round_to_bf16_matches_torch_cast_and_ties():
     # every bf16 value is a fixed point
     _, allv = all_bf16_values()
     assert np.array_equal(O.round_to("bf16", allv), allv, equal_nan=True)
+
+
+# ---------------------------------------------------------------- sanitizer build of the oracle
+
+def test_oracle_runs_clean_under_ubsan_and_bounds_checks(tmp_path):
+    """The oracle compiled with -fsanitize=undefined (traps on any finding) on ragged sizes."""
+    import subprocess
+    import sys
+    import os
+    so = tmp_path / "liboracle_ubsan.so"
+    O.build(force=True, out=str(so), extra_flags=("-fsanitize=undefined", "-fno-sanitize-recover=all", "-g"))
+    code = f"""
+import sys, numpy as np
+sys.path.insert(0, {os.path.dirname(os.path.dirname(O.__file__))!r})
+import oracle as O
+O._lib = O.load({str(so)!r})
+rng = np.random.default_rng(0)
+for n in (0, 1, 7, 63, 64, 65, 1000):
+    x = rng.standard_normal(n) * 3
+    x[:3] = [np.nan, np.inf, -np.inf][:min(3, n)]
+    g = rng.standard_normal(n)
+    for kind in ("gelu_tanh", "gelu_erf", "silu"):
+        for dtype in ("fp32", "bf16"):
+            ye, ys, m = O.invact_fwd(kind, dtype, x)
+            O.invact_bwd(kind, ys, m, g)
+            a, s, h, m2 = O.glu_fwd(kind, dtype, x, g)
+            O.glu_bwd(kind, s, g, m2, g)
+            _, yt = O.pbit_fwd(kind, dtype, x)
+            O.pbit_bwd(kind, dtype, yt, g)
+        O.finv(kind, O.f(kind, x), O.indicator(kind, x))
+    assert O.unpack(O.pack((x < 0).astype(np.uint8)), n).sum() == (x < 0).sum()
+print("clean")
+"""
+    res = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=120)
+    assert res.returncode == 0 and "clean" in res.stdout, res.stderr[-2000:]
