@@ -24,10 +24,32 @@ BYTES = {  # algorithmic bytes per element: (fp32, bf16)
 }
 
 
-def timeit(fn, iters):
+def timeit(fn, iters, graph=False):
     for _ in range(3):
         fn()
     torch.cuda.synchronize()
+    if graph:
+        # the launches are recorded once and replayed: what a launch-bound caller would do
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            fn()
+            side.synchronize()
+            with torch.cuda.graph(g, stream=side):
+                for _ in range(iters):
+                    fn()
+        torch.cuda.synchronize()
+        fn, iters_per_call = g.replay, iters
+        ts = []
+        for _ in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1) / iters_per_call)
+        return sorted(ts)[1]
     ts = []
     for _ in range(3):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -49,6 +71,7 @@ def main():
     ap.add_argument("--entries", nargs="+", default=list(BYTES))
     ap.add_argument("--blocks-per-cu", type=int, nargs="+", default=[0])
     ap.add_argument("--lib", nargs="*", default=[None], help="alternative builds of libinvact.so to compare")
+    ap.add_argument("--graph", action="store_true", help="time replays of a HIP graph holding the launches")
     args = ap.parse_args()
     torch.cuda.set_device(0)
     sizes = [1 << s for s in args.sizes] + list(args.elements)
@@ -85,10 +108,10 @@ def main():
                         for bpc in args.blocks_per_cu:
                             B.set_blocks_per_cu(bpc)
                             B.invact_fwd(kind, a, y=o2, mask=mask)  # restore the mask the backward reads
-                            ms = timeit(calls[entry], iters)
+                            ms = timeit(calls[entry], iters, args.graph)
                             nbytes = n * BYTES[entry][0 if dt == "fp32" else 1]
                             gbs = nbytes / ms / 1e6
-                            note = "cache" if n <= (1 << 24) else ""
+                            note = ("cache" if n <= (1 << 24) else "") + (" graph" if args.graph else "")
                             print(f"{tag} {entry:17s} {kind:9s} {dt} n={n:<10d} bpc={bpc:<2d} {ms * 1e3:9.2f} us "
                                   f"{gbs:7.0f} GB/s {100 * gbs / PEAK:5.1f}% {note}", flush=True)
                 B.set_blocks_per_cu(0)
