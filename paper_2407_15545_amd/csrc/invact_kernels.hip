@@ -1,7 +1,7 @@
 // HIP kernels and C ABI of libinvact (gfx950 only).  See include/invact.h for
 // the contract of every entry point.
 //
-// Kernel shape.  All four kernels are pure streaming maps, bound by HBM
+// Kernel shape.  All kernels are pure streaming maps, bound by HBM
 // bandwidth, so they share one skeleton.  The unit of work of a wavefront is a
 // "wave tile" of 512 consecutive elements = 64 mask bytes = eight 64-bit mask
 // words; each lane owns 8 of those elements (its "chunk"):

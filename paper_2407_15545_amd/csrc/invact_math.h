@@ -91,7 +91,7 @@ __device__ __forceinline__ float act_fast(float x)
         float E = hw_exp2((x * x) * (-0.5f * kLog2e));            // exp(-z^2)
         u = (med3(x, -FLT_MAX, FLT_MAX) * (g * w)) * E;
     }
-    return fmaxf(x, -0.0f) - fabsf(u);
+    return med3(x, -0.0f, INFINITY) - fabsf(u);      // max(x, -0) in one instruction; a NaN x comes through u
 }
 
 // ---------------------------------------------------------------------------
@@ -187,9 +187,10 @@ __device__ __forceinline__ float cubic_exp2(const float (&t)[4], float yt)
 //   small  q_right(y) - 1, i.e. h (GELU) or h (1 - y) (SiLU), with a relative
 //          error of a few ulp of ITSELF: the better representation once |small|
 //          is well below 1 (q near or above 1)
-// Clamps are NaN-dropping medians; the callers put a NaN y back.  yt is clamped
-// to [0, 64]: the exponential factor is exactly 0 beyond, and +inf must not
-// meet that 0.
+// Clamps are NaN-dropping medians (one instruction each), so a NaN y leaves qr
+// finite; ql is NaN for a NaN y (through the 2y term / the + y term), and the
+// callers select ql whenever y is NaN.  yt is clamped to [0, 64]: the
+// exponential factor is exactly 0 beyond, and +inf must not meet that 0.
 struct QParts { float ql, qr, small; };
 
 template <int KIND, int PREC>
@@ -201,7 +202,7 @@ __device__ __forceinline__ QParts q_parts(float y, bool left)
         const auto& L = cst::silu_left;
         const auto& R = cst::silu_right;
         (void)left;
-        float yc = fminf(y, 64.0f);
+        float yc = med3(y, -INFINITY, 64.0f);        // min(y, 64) in one instruction
         float yt = med3(y - fT, 0.0f, 64.0f);
         float sq = hw_sqrt(yt);
         // Eq. (8) as 1 + h (1 - y), h = (c0 + r) E
@@ -210,9 +211,9 @@ __device__ __forceinline__ QParts q_parts(float y, bool left)
         float h = fmaf(r, E, R[0] * E);
         out.qr    = fmaf(-yc, h, fmaf(r, E, fmaf(R[0], E, 1.0f)));
         out.small = h * (1.0f - yc);
-        // Eq. (7): (c0 + c1 sqrt(yt) + c2 yt + c3 yt^2) (1 - y) + y
+        // Eq. (7): (c0 + c1 sqrt(yt) + c2 yt + c3 yt^2) (1 - y) + y   (y itself: a NaN must show here)
         float A = fmaf(yt, fmaf(L[3], yt, L[2]), fmaf(L[1], sq, L[0]));
-        out.ql = fmaf(A, 1.0f - yc, yc);
+        out.ql = fmaf(A, 1.0f - y, y);
     } else {
         const auto& L = cst::gelu_left;
         const auto& R = cst::gelu_right;
@@ -234,7 +235,7 @@ __device__ __forceinline__ QParts q_parts(float y, bool left)
             out.small = fmaf(R[1], sE, fmaf(c2y, E, R[0] * E));
         }
         // Eq. (5): c0 sqrt(y + c1) (2y + c2 sqrt(-y)) (|c3 y^2 + |c4 y + c5| + c6| + c7)
-        float s2 = hw_sqrt(fmaxf(-y, 0.0f));
+        float s2 = hw_sqrt(med3(-y, 0.0f, FLT_MAX));
         float B  = fmaf(L[2], s2, y + y);
         float inner = fabsf(fmaf(L[4], y, L[5]));
         float outer = fabsf(fmaf(L[3], y * y, inner) + L[6]) + L[7];
@@ -259,16 +260,15 @@ template <int KIND, int PREC>
 __device__ __forceinline__ float times_q(float g, float y, bool left)
 {
     QParts p = q_parts<KIND, PREC>(y, left);
-    float out;
+    const bool take_left = left || (y != y);                   // a NaN y must give NaN: ql carries it
     if constexpr (PREC == FAST) {
-        out = g * (left ? p.ql : p.qr);
+        return g * (take_left ? p.ql : p.qr);
     } else {
-        const bool direct = left || !(fabsf(p.small) < 0.25f);
-        float base  = left ? p.ql : (direct ? p.qr : 1.0f);
+        const bool direct = take_left || !(fabsf(p.small) < 0.25f);
+        float base  = take_left ? p.ql : (direct ? p.qr : 1.0f);
         float delta = direct ? 0.0f : p.small;
-        out = fmaf(g, base, g * delta);
+        return fmaf(g, base, g * delta);
     }
-    return nan_through(y, out);
 }
 
 // (a * b) * q  (gated backward: a = grad_h, b = up)
@@ -276,17 +276,17 @@ template <int KIND, int PREC>
 __device__ __forceinline__ float times_q(float a, float b, float y, bool left)
 {
     QParts p = q_parts<KIND, PREC>(y, left);
-    float g = a * b, out;
+    const bool take_left = left || (y != y);
+    float g = a * b;
     if constexpr (PREC == FAST) {
-        out = g * (left ? p.ql : p.qr);
+        return g * (take_left ? p.ql : p.qr);
     } else {
-        const bool direct = left || !(fabsf(p.small) < 0.25f);
-        float base  = left ? p.ql : (direct ? p.qr : 1.0f);
+        const bool direct = take_left || !(fabsf(p.small) < 0.25f);
+        float base  = take_left ? p.ql : (direct ? p.qr : 1.0f);
         float delta = direct ? 0.0f : p.small;
         float e = fmaf(a, b, -g);                              // a b = g + e exactly
-        out = fmaf(g, base, fmaf(g, delta, e * (base + delta)));
+        return fmaf(g, base, fmaf(g, delta, e * (base + delta)));
     }
-    return nan_through(y, out);
 }
 
 }  // namespace invact_dev
