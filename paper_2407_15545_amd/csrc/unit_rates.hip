@@ -32,7 +32,6 @@ template <int OP> __global__ __launch_bounds__(256) void k(float* out, float see
             if (OP == 13) asm volatile("v_rcp_f32 %0, %0" : "+v"(f[i]));
             if (OP == 14) asm volatile("v_ldexp_f32 %0, %0, 1" : "+v"(f[i]));
             if (OP == 15) asm volatile("v_med3_f32 %0, %0, %0, %0" : "+v"(f[i]));
-            if (OP == 16) asm volatile("v_pk_fma_f32 %0, %0, %0, %0" : "+v"(d[i]));
             if (OP == 17) asm volatile("v_fmac_f32 %0, %1, %1" : "+v"(f[i]) : "v"(f[(i+1)%CH]));
             if (OP == 18) asm volatile("v_bfe_u32 %0, %0, 3, 1" : "+v"(f[i]));
             if (OP == 19) asm volatile("v_lshlrev_b32 %0, 16, %0" : "+v"(f[i]));
@@ -62,7 +61,7 @@ template <int OP> void run(const char* name, float* out) {
 }
 int main() {
     float* out; CK(hipMalloc(&out, 4096));
-    run<0>("v_fma_f32", out); run<11>("v_mul_f32", out); run<17>("v_fmac_f32", out); run<16>("v_pk_fma_f32 (x2)", out);
+    run<0>("v_fma_f32", out); run<11>("v_mul_f32", out); run<17>("v_fmac_f32", out);
     run<1>("v_fma_f64", out); run<2>("v_mul_f64", out); run<3>("v_add_f64", out);
     run<4>("v_cvt_f64_f32", out); run<5>("v_cvt_f32_f64", out); run<7>("v_rcp_f64", out);
     run<6>("v_exp_f32", out); run<8>("v_sqrt_f32", out); run<13>("v_rcp_f32", out);
