@@ -13,7 +13,8 @@ KINDS = {"gelu_tanh": 0, "gelu_erf": 1, "silu": 2}
 DTYPES = {torch.float32: 0, torch.bfloat16: 1}
 DTYPE_NAMES = {"fp32": torch.float32, "bf16": torch.bfloat16}
 
-_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libinvact.so")
+# INVACT_LIB selects another build of the same library (used to compare build variants)
+_LIB_PATH = os.environ.get("INVACT_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "libinvact.so")
 _lib = None
 
 _vp, _sz, _int = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
