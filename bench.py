@@ -28,8 +28,8 @@ WORKLOAD = "swiglu_bf16_4x4096x14336"
 BYTES_FWD, BYTES_BWD = 8.125, 10.125          # per element, bf16
 # HBM bytes one swiglu_invact_bwd launch moves on the full workload, from rocprofv3's
 # FETCH_SIZE and WRITE_SIZE counters scaled by their readings for a plain copy
-# (profiles/swiglu_bf16_4x4096x14336.md): 1442.6 MB read + 939.5 MB written.
-TRAFFIC_BWD_FULL = 2382.1e6
+# (profiles/swiglu_bf16_4x4096x14336.md): 1438.7 MB read + 939.5 MB written.
+TRAFFIC_BWD_FULL = 2378.3e6
 
 
 def cpu_baseline(w, n_slice):

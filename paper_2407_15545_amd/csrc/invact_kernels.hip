@@ -70,9 +70,15 @@ template <class T> __device__ __forceinline__ void st(T* p, T v)
 {
     if constexpr (kNonTemporal) __builtin_nontemporal_store(v, p); else *p = v;
 }
+// The mask moves 64 bytes per wavefront and step, half a cache line: it goes through the cache
+// so that the two halves of a line are written (read) to (from) HBM once.
 __device__ __forceinline__ void st_mask(uint8_t* p, uint8_t v)
 {
     if constexpr (kNonTemporal && INVACT_MASK_NT != 0) __builtin_nontemporal_store(v, p); else *p = v;
+}
+__device__ __forceinline__ uint8_t ld_mask(const uint8_t* p)
+{
+    if constexpr (kNonTemporal && INVACT_MASK_NT != 0) return __builtin_nontemporal_load(p); else return *p;
 }
 
 // value of the neighbouring lane (lane ^ 1); every lane of the quad must be active
@@ -130,7 +136,7 @@ template <> struct Storage<INVACT_FP32> {
     }
     static __device__ __forceinline__ uint32_t load_mask(const uint8_t* mask, size_t c)
     {
-        const uint32_t own = ld(mask + mask_index(c));
+        const uint32_t own = ld_mask(mask + mask_index(c));
         const uint32_t other = swap_with_neighbour(own);
         return (c & 1) ? ((other >> 4) | (own & 0xF0u)) : ((own & 0xFu) | ((other & 0xFu) << 4));
     }
@@ -185,7 +191,7 @@ template <> struct Storage<INVACT_BF16> {
            u32x4{pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7])});
     }
     static __device__ __forceinline__ void store_mask(uint8_t* mask, size_t c, uint32_t m) { st_mask(mask + c, (uint8_t)m); }
-    static __device__ __forceinline__ uint32_t load_mask(const uint8_t* mask, size_t c) { return ld(mask + c); }
+    static __device__ __forceinline__ uint32_t load_mask(const uint8_t* mask, size_t c) { return ld_mask(mask + c); }
     static __device__ __forceinline__ float load1(const void* p, size_t i)
     {
         return __uint_as_float((uint32_t) reinterpret_cast<const uint16_t*>(p)[i] << 16);
