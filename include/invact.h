@@ -127,12 +127,19 @@ int invact_pbit_bwd(int kind, int dtype, const void* y, const void* grad_y, void
                     size_t n, hipStream_t stream);
 
 /*
- * Launch tuning (process-wide, for benchmarking).  By default every 256-thread
- * workgroup handles one tile and retires.  blocks_per_cu in 1..64 switches to
- * a persistent grid of that many workgroups per compute unit striding over
- * the tensor; 0 restores the default.  Results are bit-identical either way.
- * Returns blocks_per_cu, or a negative number if it is out of range.
+ * Launch tuning (process-wide, for benchmarking; results are bit-identical
+ * whatever is set).  By default a workgroup is one wavefront that handles one
+ * tile and retires, and every entry point caps the number of such workgroups
+ * resident on a compute unit at the value measured best for it on MI355X.
+ *
+ * invact_set_resident_blocks: blocks in 1..32 forces that cap for all entry
+ * points (32 = the hardware's own limit, i.e. no cap); 0 restores the
+ * defaults.  invact_set_blocks_per_cu: blocks_per_cu in 1..64 switches to a
+ * persistent grid of that many workgroups per compute unit striding over the
+ * tensor (uncapped); 0 restores the default.  Both return their argument, or
+ * a negative number if it is out of range.
  */
+int invact_set_resident_blocks(int blocks);
 int invact_set_blocks_per_cu(int blocks_per_cu);
 
 #ifdef __cplusplus

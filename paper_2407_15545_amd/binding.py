@@ -22,6 +22,7 @@ _PROTOTYPES = {
     "invact_mask_bytes": (_sz, [_sz]),
     "invact_strerror": (ctypes.c_char_p, [_int]),
     "invact_set_blocks_per_cu": (_int, [_int]),
+    "invact_set_resident_blocks": (_int, [_int]),
     "invact_fwd": (_int, [_int, _int, _vp, _vp, _vp, _sz, _vp]),
     "invact_bwd": (_int, [_int, _int, _vp, _vp, _vp, _vp, _sz, _vp]),
     "geglu_invact_fwd": (_int, [_int, _int, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
@@ -101,6 +102,10 @@ def mask_bytes(n):
 
 def set_blocks_per_cu(v):
     return int(lib().invact_set_blocks_per_cu(int(v)))
+
+
+def set_resident_blocks(v):
+    return int(lib().invact_set_resident_blocks(int(v)))
 
 
 def invact_fwd(kind, x, y=None, mask=None, stream=None):

@@ -14,13 +14,27 @@
 //             different mask bytes; neighbouring lanes swap nibbles with one
 //             DPP move so that every lane again stores (or loads) one byte.
 // The canonical little-endian bit stream thus comes out of lane-local shifts.
-// Each lane keeps Op::kUnroll chunks in flight: all loads of a step are issued
+// A lane keeps Op::kShape.unroll chunks in flight: all loads of a step are issued
 // before the first store, which is also what makes element-wise in-place use
-// (y == x and the like) safe.  By default a workgroup handles one tile of
-// Op::kUnroll * 256 chunks and retires; the tensor accesses are non-temporal
-// (each byte is touched once).  The up to 511 elements past the last full wave tile
-// are handled one element per lane by the first wavefront, the mask word being
-// formed by a wave64 ballot there (and zero padding coming for free).
+// (y == x and the like) safe.  The tensor accesses are non-temporal (each byte
+// is touched once); mask bytes go through the cache, because the 64 bytes a
+// wavefront touches are half a cache line.  The up to 511 elements past the
+// last full wave tile are handled one element per lane by the first wavefront,
+// the mask word being formed by a wave64 ballot there (and zero padding coming
+// for free).
+//
+// Launch shape.  A workgroup is ONE wavefront that handles kShape.unroll wave
+// tiles and retires; the hardware dispatcher balances the load.  HBM delivers
+// the most when a compute unit has roughly 32 to 96 KiB of loads in flight and
+// no more: beyond that the streams of too many wavefronts interleave in the
+// memory channels and the rate drops by 5-10 %.  Op::kShape.resident therefore
+// caps the number of resident wavefronts per compute unit (below the 32 the
+// hardware allows) by giving each workgroup a share of the 160 KiB of LDS that
+// it never touches.  Single-wavefront workgroups matter for this: a freed slot
+// is refilled at once instead of waiting for the last wavefront of a larger
+// workgroup.  The figures in the kShape tables are the measured optima on
+// MI355X at 2^24 elements and more; below that the launch is latency-bound
+// and the shape makes no difference.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -33,34 +47,35 @@ namespace {
 
 using namespace invact_dev;
 
-// chunks in flight per lane, per kind of operation (timed on MI355X in the benchmark's
-// alternation of forward and backward launches: 4 beats 2 by 2-3 % for the gated kernels)
-#ifndef INVACT_UNROLL_FWD
-#define INVACT_UNROLL_FWD 2
-#endif
-#ifndef INVACT_UNROLL_BWD
-#define INVACT_UNROLL_BWD 2
-#endif
-#ifndef INVACT_UNROLL_GLU_FWD
-#define INVACT_UNROLL_GLU_FWD 4
-#endif
-#ifndef INVACT_UNROLL_GLU_BWD
-#define INVACT_UNROLL_GLU_BWD 4
-#endif
 #ifndef INVACT_NT
 #define INVACT_NT 1
 #endif
 #ifndef INVACT_MASK_NT
 #define INVACT_MASK_NT 0
 #endif
+#ifndef INVACT_THREADS
+#define INVACT_THREADS 64
+#endif
 #ifndef INVACT_DEFAULT_BLOCKS_PER_CU
 #define INVACT_DEFAULT_BLOCKS_PER_CU 0
 #endif
 
-constexpr int  kThreads = 256;
+constexpr int  kThreads = INVACT_THREADS;
 constexpr int  kWaveTile = 512;                   // elements per wavefront and step
 constexpr bool kNonTemporal = INVACT_NT != 0;     // every byte is touched once: keep it out of the caches
 constexpr int  kDefaultBlocksPerCu = INVACT_DEFAULT_BLOCKS_PER_CU;   // 0: one tile per workgroup
+constexpr int  kWaveSlotsPerCu = 32;              // resident wavefronts a compute unit can hold
+
+// Launch shape of an operation: wave tiles per wavefront and the cap on resident
+// workgroups per compute unit (kWaveSlotsPerCu: no cap).
+struct Shape { int unroll, resident; };
+template <int DT> constexpr Shape pick(Shape binary32, Shape bfloat16)
+{
+#ifdef INVACT_UNROLL_ALL                           // build variants for sweeps
+    binary32.unroll = bfloat16.unroll = INVACT_UNROLL_ALL;
+#endif
+    return DT == INVACT_FP32 ? binary32 : bfloat16;
+}
 
 template <class T> __device__ __forceinline__ T ld(const T* p)
 {
@@ -261,7 +276,7 @@ struct FwdOp {                       // y = f(x), s = [x < T]
         return v < KindConst<KIND>::T;
     }
     static constexpr int kMask = MASK_WRITE;
-    static constexpr int kUnroll = INVACT_UNROLL_FWD;
+    static constexpr Shape kShape = pick<DT>({2, 32}, {1, 32});
 };
 
 template <int KIND, int DT>
@@ -286,7 +301,7 @@ struct BwdOp {                       // grad_x = grad_y * q(y, s)
         return bit;
     }
     static constexpr int kMask = MASK_READ;
-    static constexpr int kUnroll = INVACT_UNROLL_BWD;
+    static constexpr Shape kShape = pick<DT>({2, 10}, {1, 32});
 };
 
 template <int KIND, int DT>
@@ -320,7 +335,7 @@ struct GluFwdOp {                    // act = f(gate), s = [gate < T], h = f(gat
         return v < KindConst<KIND>::T;
     }
     static constexpr int kMask = MASK_WRITE;
-    static constexpr int kUnroll = (DT == INVACT_BF16) ? INVACT_UNROLL_GLU_FWD : 2;   // binary32 doubles the registers per chunk
+    static constexpr Shape kShape = pick<DT>({2, 10}, {1, 16});
 };
 
 template <int KIND, int DT>
@@ -352,7 +367,7 @@ struct GluBwdOp {                    // grad_up = grad_h * act ; grad_gate = gra
         return bit;
     }
     static constexpr int kMask = MASK_READ;
-    static constexpr int kUnroll = (DT == INVACT_BF16) ? INVACT_UNROLL_GLU_BWD : 2;
+    static constexpr Shape kShape = pick<DT>({2, 8}, {1, 16});
 };
 
 // Precision-bit variant: no mask tensor, the indicator travels in bit 0 of y.
@@ -380,7 +395,7 @@ struct PbitFwdOp {                   // y = f(x) with bit 0 := [x < T]
         return false;
     }
     static constexpr int kMask = MASK_NONE;
-    static constexpr int kUnroll = INVACT_UNROLL_FWD;
+    static constexpr Shape kShape = pick<DT>({2, 32}, {1, 32});
 };
 
 template <int KIND, int DT>
@@ -404,7 +419,7 @@ struct PbitBwdOp {                   // s = bit 0 of y; grad_x = grad_y * q(y, s
         return false;
     }
     static constexpr int kMask = MASK_NONE;
-    static constexpr int kUnroll = INVACT_UNROLL_BWD;
+    static constexpr Shape kShape = pick<DT>({2, 8}, {1, 32});
 };
 
 // ---------------------------------------------------------------------------
@@ -420,7 +435,7 @@ struct PbitBwdOp {                   // s = bit 0 of y; grad_x = grad_y * q(y, s
 template <class Op, bool PERSISTENT>
 __global__ __launch_bounds__(kThreads) void stream_kernel(const Op op, const size_t n)
 {
-    constexpr int kUnroll = Op::kUnroll;
+    constexpr int kUnroll = Op::kShape.unroll;
     const size_t wave_tiles = n / kWaveTile;
     const size_t chunks = wave_tiles * 64;
 
@@ -486,6 +501,8 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(const Op op, const siz
 
 std::atomic<int> g_blocks_per_cu{kDefaultBlocksPerCu};
 std::atomic<int> g_cu_count[64];            // per device, 0 = not queried yet
+std::atomic<int> g_resident_override{0};     // 0: every operation uses its own kShape.resident
+constexpr unsigned kLdsPerCu = 160 * 1024;
 
 int cu_count()
 {
@@ -501,17 +518,40 @@ int cu_count()
 
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
+// Bytes of (unused) dynamic LDS that keep at most `resident` workgroups of a
+// kernel on one compute unit; the kernel is told once per device that it may
+// be launched with that much.
+template <class Op>
+unsigned occupancy_cap_lds(int resident)
+{
+    if (resident <= 0 || resident * (kThreads / 64) >= kWaveSlotsPerCu) return 0;   // the hardware's own limit
+    static std::atomic<uint64_t> prepared{0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+    if (!(prepared.load(std::memory_order_acquire) >> dev & 1)) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(stream_kernel<Op, false>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)kLdsPerCu) != hipSuccess) {
+            (void)hipGetLastError();
+            return 0;
+        }
+        prepared.fetch_or(uint64_t(1) << dev, std::memory_order_release);
+    }
+    return kLdsPerCu / (unsigned)resident;
+}
+
 template <class Op>
 int launch(const Op& op, size_t n, hipStream_t stream)
 {
-    constexpr int kUnroll = Op::kUnroll;
+    constexpr int kUnroll = Op::kShape.unroll;
     const size_t chunks = (n / kWaveTile) * 64;
     const int per_cu = g_blocks_per_cu.load(std::memory_order_relaxed);
     if (per_cu == 0) {
         size_t blocks = (chunks + kThreads * kUnroll - 1) / (kThreads * kUnroll);
         if (blocks == 0) blocks = 1;                          // the tail still needs a thread
         if (blocks > 0x7FFFFFFFu) return INVACT_ERR_SIZE;
-        hipLaunchKernelGGL((stream_kernel<Op, false>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, op, n);
+        const int forced = g_resident_override.load(std::memory_order_relaxed);
+        const unsigned lds = occupancy_cap_lds<Op>(forced ? forced : Op::kShape.resident);
+        hipLaunchKernelGGL((stream_kernel<Op, false>), dim3((unsigned)blocks), dim3(kThreads), lds, stream, op, n);
     } else {
         size_t blocks = (chunks + kThreads - 1) / kThreads;
         const size_t cap = (size_t)cu_count() * (size_t)per_cu;
@@ -583,6 +623,13 @@ int invact_set_blocks_per_cu(int blocks_per_cu)
     if (blocks_per_cu < 0 || blocks_per_cu > 64) return -1;
     g_blocks_per_cu.store(blocks_per_cu == 0 ? kDefaultBlocksPerCu : blocks_per_cu, std::memory_order_relaxed);
     return blocks_per_cu;
+}
+
+int invact_set_resident_blocks(int blocks)
+{
+    if (blocks < 0 || blocks > 32) return -1;
+    g_resident_override.store(blocks, std::memory_order_relaxed);
+    return blocks;
 }
 
 int invact_fwd(int kind, int dtype, const void* x, void* y, void* mask, size_t n, hipStream_t stream)

@@ -70,6 +70,8 @@ def main():
     ap.add_argument("--dtypes", nargs="+", default=["bf16", "fp32"])
     ap.add_argument("--entries", nargs="+", default=list(BYTES))
     ap.add_argument("--blocks-per-cu", type=int, nargs="+", default=[0])
+    ap.add_argument("--resident", type=int, nargs="+", default=[0],
+                    help="cap on resident workgroups per compute unit (0 = the library's default, 8 = none)")
     ap.add_argument("--lib", nargs="*", default=[None], help="alternative builds of libinvact.so to compare")
     ap.add_argument("--graph", action="store_true", help="time replays of a HIP graph holding the launches")
     args = ap.parse_args()
@@ -106,15 +108,18 @@ def main():
                     }
                     for entry in args.entries:
                         for bpc in args.blocks_per_cu:
+                          for res in args.resident:
                             B.set_blocks_per_cu(bpc)
+                            B.set_resident_blocks(res)
                             B.invact_fwd(kind, a, y=o2, mask=mask)  # restore the mask the backward reads
                             ms = timeit(calls[entry], iters, args.graph)
                             nbytes = n * BYTES[entry][0 if dt == "fp32" else 1]
                             gbs = nbytes / ms / 1e6
                             note = ("cache" if n <= (1 << 24) else "") + (" graph" if args.graph else "")
-                            print(f"{tag} {entry:17s} {kind:9s} {dt} n={n:<10d} bpc={bpc:<2d} {ms * 1e3:9.2f} us "
+                            print(f"{tag} {entry:17s} {kind:9s} {dt} n={n:<10d} bpc={bpc:<2d} res={res:<2d} {ms * 1e3:9.2f} us "
                                   f"{gbs:7.0f} GB/s {100 * gbs / PEAK:5.1f}% {note}", flush=True)
                 B.set_blocks_per_cu(0)
+                B.set_resident_blocks(0)
                 del a, b, c, o1, o2, mask
 
 
