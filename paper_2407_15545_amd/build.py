@@ -52,5 +52,13 @@ def build_tools(verbose=False):
 
 
 if __name__ == "__main__":
-    print(build(force=True, verbose=True, extra=sys.argv[1:]))
-    print(*build_tools(verbose=True), sep="\n")
+    # python -m paper_2407_15545_amd.build [-o variant.so] [-DINVACT_UNROLL_ALL=2 ...]
+    argv = sys.argv[1:]
+    if "-o" in argv:                       # a build variant for sweeps: only the library, at the given path
+        i = argv.index("-o")
+        out = os.path.abspath(argv[i + 1])
+        build(force=True, verbose=True, extra=argv[:i] + argv[i + 2:], out=out)
+        print(out)
+    else:
+        print(build(force=True, verbose=True, extra=argv))
+        print(*build_tools(verbose=True), sep="\n")

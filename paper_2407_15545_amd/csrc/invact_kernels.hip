@@ -335,7 +335,7 @@ struct GluFwdOp {                    // act = f(gate), s = [gate < T], h = f(gat
         return v < KindConst<KIND>::T;
     }
     static constexpr int kMask = MASK_WRITE;
-    static constexpr Shape kShape = pick<DT>({2, 10}, {1, 16});
+    static constexpr Shape kShape = pick<DT>({2, 7}, {1, 16});
 };
 
 template <int KIND, int DT>
@@ -367,7 +367,7 @@ struct GluBwdOp {                    // grad_up = grad_h * act ; grad_gate = gra
         return bit;
     }
     static constexpr int kMask = MASK_READ;
-    static constexpr Shape kShape = pick<DT>({2, 8}, {1, 16});
+    static constexpr Shape kShape = pick<DT>({2, 7}, {1, 16});
 };
 
 // Precision-bit variant: no mask tensor, the indicator travels in bit 0 of y.

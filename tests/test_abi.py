@@ -88,6 +88,14 @@ def test_blocks_per_cu_range():
         assert B.set_blocks_per_cu(0) == 0
 
 
+def test_resident_blocks_range():
+    try:
+        assert B.set_resident_blocks(16) == 16 and B.set_resident_blocks(32) == 32
+        assert B.set_resident_blocks(33) < 0 and B.set_resident_blocks(-1) < 0
+    finally:
+        assert B.set_resident_blocks(0) == 0
+
+
 def test_binding_raises_with_the_library_message():
     with pytest.raises(B.InvactError) as e:
         B._check(ERR_ALIGN)

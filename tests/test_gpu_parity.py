@@ -273,7 +273,8 @@ def same_bits(a, b):
 
 @pytest.mark.parametrize("dtype", DTYPES)
 def test_other_stream_and_grid_shapes_give_identical_bits(dtype):
-    """Every entry point on a side stream and as a persistent grid of several sizes: same bits as the default."""
+    """Every entry point on a side stream, with other caps on resident workgroups and as a persistent grid of
+    several sizes: same bits as the default."""
     n = (1 << 22) + 13 * 512 + 77
     kind = "gelu_erf"
     x, up, g = (PT.to_device(draw(n, 41 + i, dtype), dtype) for i in range(3))
@@ -292,6 +293,15 @@ def test_other_stream_and_grid_shapes_give_identical_bits(dtype):
     with torch.cuda.stream(side):
         got = run_all()
     assert all(same_bits(a, b) for a, b in zip(ref, got))
+    try:
+        for cap in (1, 5, 16, 32):
+            PT.say(f"  at most {cap} resident workgroups per compute unit")
+            assert B.set_resident_blocks(cap) == cap
+            got = run_all()
+            assert all(same_bits(a, b) for a, b in zip(ref, got)), cap
+        assert B.set_resident_blocks(33) < 0 and B.set_resident_blocks(-1) < 0
+    finally:
+        B.set_resident_blocks(0)
     try:
         for bpc in (1, 3, 16, 64):
             PT.say(f"  persistent grid, {bpc} workgroups per compute unit")
