@@ -44,9 +44,26 @@ def cpu_baseline(w, n_slice):
     ae, as_, he, m = O.glu_fwd("silu", "bf16", gate, up)
     gg, gu = O.glu_bwd("silu", as_, up, m, gh)
     dt = time.perf_counter() - t0
-    return {"value": round(n_slice * (BYTES_FWD + BYTES_BWD) / dt / 1e9, 4), "unit": "GB/s",
-            "cores": O.num_threads(), "kind": "oracle",
-            "sample": f"first {n_slice} elements of the workload, forward+backward, {dt:.2f} s"}
+    out = {"value": round(n_slice * (BYTES_FWD + BYTES_BWD) / dt / 1e9, 4), "unit": "GB/s",
+           "cores": O.num_threads(), "kind": "oracle",
+           "sample": f"first {n_slice} elements of the workload, forward+backward, {dt:.2f} s"}
+    # the same code on one thread, on a smaller slice (the OpenMP runtime is told so; the oracle is untouched)
+    n1 = min(n_slice, 1 << 22)
+    try:
+        import ctypes
+        omp = ctypes.CDLL("libgomp.so.1")
+        threads = O.num_threads()
+        omp.omp_set_num_threads(1)
+        t0 = time.perf_counter()
+        _, as1, _, m1 = O.glu_fwd("silu", "bf16", gate[:n1], up[:n1])
+        O.glu_bwd("silu", as1, up[:n1], m1, gh[:n1])
+        dt1 = time.perf_counter() - t0
+        omp.omp_set_num_threads(threads)
+        out["single_thread"] = {"value": round(n1 * (BYTES_FWD + BYTES_BWD) / dt1 / 1e9, 4), "unit": "GB/s",
+                                "sample": f"first {n1} elements, {dt1:.2f} s"}
+    except OSError:
+        pass
+    return out
 
 
 def main():
@@ -57,6 +74,9 @@ def main():
     ap.add_argument("--cpu-elems", type=int, default=1 << 28, help="elements of the CPU-baseline slice (0 = skip)")
     ap.add_argument("--blocks-per-cu", type=int, default=0)
     ap.add_argument("--elements", type=int, default=0, help="override the element count (debugging only)")
+    ap.add_argument("--unfused-iters", type=int, default=20,
+                    help="after the timed steps, time the unfused forward (invact_fwd + a separate multiply) this "
+                         "many times for comparison (0 = skip); never part of `value`")
     ap.add_argument("--calibration-copies", type=int, default=0,
                     help="after the timed steps, run this many plain device copies of one tensor (reads and "
                          "writes 2 bytes per element each): the known traffic that rocprofv3's FETCH_SIZE / "
@@ -104,6 +124,23 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
+    # The forward as two launches, for comparison: invact_fwd(silu) saves act and the mask, then a
+    # separate element-wise multiply (torch's) reads act and up and writes h: 4.125 + 6 bytes per element.
+    unfused = None
+    if args.unfused_iters:
+        def unfused_fwd():
+            B.invact_fwd("silu", gate, y=act, mask=mask, stream=stream)
+            torch.mul(act, up, out=h)
+        for _ in range(3):
+            unfused_fwd()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(args.unfused_iters):
+            unfused_fwd()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        unfused = e0.elapsed_time(e1) / args.unfused_iters
+
     for _ in range(args.calibration_copies):
         act.copy_(gate)
     torch.cuda.synchronize()
@@ -132,6 +169,10 @@ def main():
                      "traffic": TRAFFIC_BWD_FULL if n == synth.numel(WORKLOAD) else None,
                      "algorithmic_bytes": n * BYTES_BWD, "avg_launch_ms": round(bwd_ms, 5)},
     }
+    if unfused is not None:
+        out["config"]["unfused_fwd"] = {"ms": round(unfused, 5), "bytes_per_element": 10.125,
+                                        "GB/s": round(n * 10.125 / (unfused * 1e-3) / 1e9, 1),
+                                        "what": "invact_fwd(silu) + torch.mul, for comparison with fwd_kernel"}
     if args.cpu_elems:
         out["cpu_baseline"] = cpu_baseline(w, min(args.cpu_elems, n))
     print(json.dumps(out), flush=True)
