@@ -5,6 +5,7 @@ device memory (tensors) and streams, nothing else; there is no fallback: if the
 library is missing, loading it raises.
 """
 import ctypes
+import functools
 import os
 
 import torch
@@ -75,6 +76,24 @@ def _stream(stream):
     return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
 
 
+class _on_device:
+    """Makes the tensors' device current for the call; free when it already is."""
+    __slots__ = ("index", "prev")
+
+    def __init__(self, device):
+        self.index = device.index
+
+    def __enter__(self):
+        self.prev = torch.cuda.current_device()
+        if self.prev != self.index:
+            torch.cuda.set_device(self.index)
+
+    def __exit__(self, *exc):
+        if self.prev != self.index:
+            torch.cuda.set_device(self.prev)
+        return False
+
+
 def _tensors(*ts):
     first = ts[0]
     for t in ts:
@@ -96,6 +115,7 @@ def _mask_arg(mask, n, like):
     return mask
 
 
+@functools.lru_cache(maxsize=256)
 def mask_bytes(n):
     return int(lib().invact_mask_bytes(n))
 
@@ -113,7 +133,7 @@ def invact_fwd(kind, x, y=None, mask=None, stream=None):
     y = torch.empty_like(x) if y is None else y
     dt, n = _tensors(x, y)
     mask = _mask_arg(mask, n, x)
-    with torch.cuda.device(x.device):
+    with _on_device(x.device):
         _check(lib().invact_fwd(_kind(kind), dt, x.data_ptr(), y.data_ptr(), mask.data_ptr(), n, _stream(stream)))
     return y, mask
 
@@ -123,7 +143,7 @@ def invact_bwd(kind, y, mask, grad_y, grad_x=None, stream=None):
     grad_x = torch.empty_like(grad_y) if grad_x is None else grad_x
     dt, n = _tensors(y, grad_y, grad_x)
     mask = _mask_arg(mask, n, y)
-    with torch.cuda.device(y.device):
+    with _on_device(y.device):
         _check(lib().invact_bwd(_kind(kind), dt, y.data_ptr(), mask.data_ptr(), grad_y.data_ptr(),
                                 grad_x.data_ptr(), n, _stream(stream)))
     return grad_x
@@ -135,7 +155,7 @@ def geglu_invact_fwd(kind, gate, up, act=None, h=None, mask=None, stream=None):
     h = torch.empty_like(gate) if h is None else h
     dt, n = _tensors(gate, up, act, h)
     mask = _mask_arg(mask, n, gate)
-    with torch.cuda.device(gate.device):
+    with _on_device(gate.device):
         _check(lib().geglu_invact_fwd(_kind(kind), dt, gate.data_ptr(), up.data_ptr(), act.data_ptr(),
                                       h.data_ptr(), mask.data_ptr(), n, _stream(stream)))
     return act, h, mask
@@ -147,7 +167,7 @@ def geglu_invact_bwd(kind, act, up, mask, grad_h, grad_gate=None, grad_up=None, 
     grad_up = torch.empty_like(act) if grad_up is None else grad_up
     dt, n = _tensors(act, up, grad_h, grad_gate, grad_up)
     mask = _mask_arg(mask, n, act)
-    with torch.cuda.device(act.device):
+    with _on_device(act.device):
         _check(lib().geglu_invact_bwd(_kind(kind), dt, act.data_ptr(), up.data_ptr(), mask.data_ptr(),
                                       grad_h.data_ptr(), grad_gate.data_ptr(), grad_up.data_ptr(), n,
                                       _stream(stream)))
@@ -158,7 +178,7 @@ def invact_pbit_fwd(kind, x, y=None, stream=None):
     """Precision-bit forward: y = f(x) with the indicator in y's lowest bit.  Returns y."""
     y = torch.empty_like(x) if y is None else y
     dt, n = _tensors(x, y)
-    with torch.cuda.device(x.device):
+    with _on_device(x.device):
         _check(lib().invact_pbit_fwd(_kind(kind), dt, x.data_ptr(), y.data_ptr(), n, _stream(stream)))
     return y
 
@@ -167,7 +187,7 @@ def invact_pbit_bwd(kind, y, grad_y, grad_x=None, stream=None):
     """Precision-bit backward: grad_x = grad_y * q(y, bit 0 of y).  Returns grad_x."""
     grad_x = torch.empty_like(grad_y) if grad_x is None else grad_x
     dt, n = _tensors(y, grad_y, grad_x)
-    with torch.cuda.device(y.device):
+    with _on_device(y.device):
         _check(lib().invact_pbit_bwd(_kind(kind), dt, y.data_ptr(), grad_y.data_ptr(), grad_x.data_ptr(), n,
                                      _stream(stream)))
     return grad_x
@@ -178,7 +198,7 @@ def swiglu_invact_fwd(gate, up, act=None, h=None, mask=None, stream=None):
     h = torch.empty_like(gate) if h is None else h
     dt, n = _tensors(gate, up, act, h)
     mask = _mask_arg(mask, n, gate)
-    with torch.cuda.device(gate.device):
+    with _on_device(gate.device):
         _check(lib().swiglu_invact_fwd(dt, gate.data_ptr(), up.data_ptr(), act.data_ptr(), h.data_ptr(),
                                        mask.data_ptr(), n, _stream(stream)))
     return act, h, mask
@@ -189,7 +209,7 @@ def swiglu_invact_bwd(act, up, mask, grad_h, grad_gate=None, grad_up=None, strea
     grad_up = torch.empty_like(act) if grad_up is None else grad_up
     dt, n = _tensors(act, up, grad_h, grad_gate, grad_up)
     mask = _mask_arg(mask, n, act)
-    with torch.cuda.device(act.device):
+    with _on_device(act.device):
         _check(lib().swiglu_invact_bwd(dt, act.data_ptr(), up.data_ptr(), mask.data_ptr(), grad_h.data_ptr(),
                                        grad_gate.data_ptr(), grad_up.data_ptr(), n, _stream(stream)))
     return grad_gate, grad_up

@@ -1,0 +1,168 @@
+"""Block-level timing of the drop-in layers (Section 4.1, Table 1, rows 1-4; set-ups of the appendix).
+
+    python -m paper_2407_15545_amd.block_bench [--dtypes bf16 fp32] [--iters 20]
+
+For each architecture block the forward + backward time of one training step
+is measured with torch's activation, with the InvAct layer and with the
+precision-bit InvAct layer in its place:
+
+  plain        the nonlinearity alone on 2^25 elements (the paper's size), eagerly and replayed from a
+               HIP graph (an MI355X needs ~60 us for this size, about what the Python call path of
+               one step costs, so the eager figure measures the host), and on 2^28 elements
+  linear+act   Linear(2^10 -> 2^10) + nonlinearity, batch 2^15
+  mlp          Linear(2^10 -> 4*2^10) + nonlinearity + Linear(4*2^10 -> 2^10), batch 2^15
+  geglu        act(Linear(2^10 -> 4*2^10)) * Linear(2^10 -> 4*2^10), batch 2^15; for InvAct
+               also with the fused gated kernel (one launch for activation and product)
+
+The GEMMs are torch's (hipBLASLt / rocBLAS); only the activation differs between
+the columns.  Inputs and weights are seeded random numbers: the table is about
+time, and the time of these kernels does not depend on the values.  The
+BERT and Llama rows of the table need the models and are not reproduced.
+"""
+import argparse
+import statistics
+
+import torch
+
+from . import nn as invact_nn
+
+BATCH, DIM = 1 << 15, 1 << 10
+
+
+class Plain(torch.nn.Module):
+    def __init__(self, act):
+        super().__init__()
+        self.act = act
+
+    def forward(self, x):
+        return self.act(x)
+
+
+class LinearAct(torch.nn.Module):
+    def __init__(self, act):
+        super().__init__()
+        self.fc = torch.nn.Linear(DIM, DIM)
+        self.act = act
+
+    def forward(self, x):
+        return self.act(self.fc(x))
+
+
+class Mlp(torch.nn.Module):
+    def __init__(self, act):
+        super().__init__()
+        self.fc1 = torch.nn.Linear(DIM, 4 * DIM)
+        self.act = act
+        self.fc2 = torch.nn.Linear(4 * DIM, DIM)
+
+    def forward(self, x):
+        return self.fc2(self.act(self.fc1(x)))
+
+
+class GeGlu(torch.nn.Module):
+    """act(x W_gate) * (x W_up); `glu`, if given, computes activation and product in one call."""
+
+    def __init__(self, act=None, glu=None):
+        super().__init__()
+        self.gate = torch.nn.Linear(DIM, 4 * DIM)
+        self.up = torch.nn.Linear(DIM, 4 * DIM)
+        self.act, self.glu = act, glu
+
+    def forward(self, x):
+        if self.glu is not None:
+            return self.glu(self.gate(x), self.up(x))
+        return self.act(self.gate(x)) * self.up(x)
+
+
+def time_block(module, x, iters, groups=5, graph=False):
+    """Median over groups of the mean forward + backward time (ms) of `iters` consecutive steps.
+
+    graph=True: the step is captured once into a HIP graph and the replays are timed."""
+    def step():
+        y = module(x)
+        y.backward(grad)
+        x.grad = None
+        for p in module.parameters():
+            p.grad = None
+    with torch.no_grad():
+        grad = torch.randn_like(module(x))
+    if graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for _ in range(3):
+                step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        captured = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(captured):
+            y = module(x)
+            y.backward(grad)
+        step = captured.replay
+    for _ in range(3):
+        step()
+    torch.cuda.synchronize()
+    times = []
+    for _ in range(groups):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            step()
+        e1.record()
+        torch.cuda.synchronize()
+        times.append(e0.elapsed_time(e1) / iters)
+    return statistics.median(times)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--dtypes", nargs="+", default=["bf16", "fp32"])
+    ap.add_argument("--iters", type=int, default=20)
+    ap.add_argument("--approximate", default="none", choices=["none", "tanh"])
+    ap.add_argument("--blocks", nargs="+", default=["plain", "linear", "mlp", "geglu"])
+    args = ap.parse_args()
+    torch.cuda.set_device(0)
+    torch.backends.cuda.matmul.allow_tf32 = False
+    kind = "gelu_erf" if args.approximate == "none" else "gelu_tanh"
+
+    acts = {
+        "torch": lambda: torch.nn.GELU(approximate=args.approximate),
+        "invact": lambda: invact_nn.InvActGELU(approximate=args.approximate),
+        "pbit": lambda: invact_nn.InvActGELU(approximate=args.approximate, precision_bit=True),
+    }
+    blocks = {
+        "plain GELU (2^25)": (Plain, (1 << 25,)),
+        "plain GELU (2^25), graph": (Plain, (1 << 25,)),
+        "plain GELU (2^28)": (Plain, (1 << 28,)),
+        "Linear + GELU": (LinearAct, (BATCH, DIM)),
+        "Transformer MLP block": (Mlp, (BATCH, DIM)),
+        "GeGLU": (GeGlu, (BATCH, DIM)),
+    }
+    print(f"{'block':26s} {'dtype':5s} {'torch ms':>9s} {'InvAct ms':>18s} {'precision-bit ms':>18s} {'InvAct fused ms':>18s}", flush=True)
+    for dt in args.dtypes:
+        td = {"bf16": torch.bfloat16, "fp32": torch.float32}[dt]
+        for name, (cls, shape) in blocks.items():
+            if not any(name.lower().replace(" ", "").startswith(b) or b in name.lower() for b in args.blocks):
+                continue
+            torch.manual_seed(0)
+            x = torch.randn(*shape, device="cuda", dtype=torch.float32).to(td).requires_grad_(True)
+            res = {}
+            for col, make in acts.items():
+                torch.manual_seed(1)
+                module = cls(make()).to(device="cuda", dtype=td)
+                res[col] = time_block(module, x, args.iters, graph=name.endswith("graph"))
+                del module
+            if cls is GeGlu:
+                torch.manual_seed(1)
+                module = GeGlu(glu=invact_nn.InvActGLU(kind)).to(device="cuda", dtype=td)
+                res["fused"] = time_block(module, x, args.iters)
+                del module
+            base = res["torch"]
+            cell = lambda k: f"{res[k]:8.3f} ({100 * (res[k] / base - 1):+6.2f}%)" if k in res else ""
+            print(f"{name:26s} {dt:5s} {base:9.3f} {cell('invact'):>18s} {cell('pbit'):>18s} {cell('fused'):>18s}", flush=True)
+            del x
+            torch.cuda.empty_cache()
+
+
+if __name__ == "__main__":
+    main()

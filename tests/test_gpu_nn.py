@@ -87,3 +87,29 @@ def test_saved_activation_memory_of_a_transformer_mlp_stack():
 def test_layers_refuse_cpu_tensors():
     with pytest.raises((ValueError, RuntimeError)):
         inv.InvActSiLU()(torch.randn(8))
+
+
+def test_block_bench_blocks_match_torch_and_time():
+    """The blocks of the block-level timing script: same outputs as with torch's GELU up to the storage
+    rounding, gradients up to the approximation error of q, and the timer (eager and graph replay) runs."""
+    from paper_2407_15545_amd import block_bench as BB
+    torch.manual_seed(0)
+    x = torch.randn(256, BB.DIM, device="cuda", dtype=torch.bfloat16, requires_grad=True)
+    for cls in (BB.LinearAct, BB.Mlp, BB.GeGlu):
+        torch.manual_seed(1)
+        ref = cls(torch.nn.GELU()).to(device="cuda", dtype=torch.bfloat16)
+        torch.manual_seed(1)
+        got = cls(inv.InvActGELU()).to(device="cuda", dtype=torch.bfloat16)
+        yr, yg = ref(x), got(x)
+        assert torch.allclose(yr.float(), yg.float(), rtol=2e-2, atol=2e-2)
+        g = torch.randn_like(yr)
+        (gr,) = torch.autograd.grad(yr, x, g)
+        (gg,) = torch.autograd.grad(yg, x, g)
+        rel = (gr.float() - gg.float()).norm() / gr.float().norm()
+        assert rel < 3e-2, (cls.__name__, float(rel))
+    torch.manual_seed(1)
+    fused = BB.GeGlu(glu=inv.InvActGLU("gelu_erf")).to(device="cuda", dtype=torch.bfloat16)
+    assert torch.allclose(fused(x).float(), yg.float(), rtol=2e-2, atol=2e-2)
+    xs = torch.randn(1 << 16, device="cuda", dtype=torch.bfloat16, requires_grad=True)
+    for graph in (False, True):
+        assert BB.time_block(BB.Plain(inv.InvActGELU()), xs, iters=3, groups=2, graph=graph) > 0
