@@ -85,9 +85,9 @@ __device__ __forceinline__ float act_fast(float x)
         // Phi(-|x|) = erfc(z) / 2 = erfcx(z) exp(-z^2) / 2 with z = |x| / sqrt 2
         constexpr float pz = (float)(cst::erfcx_fast_p * kInvSqrt2);
         float w = hw_rcp(fmaf(pz, fabsf(x), 1.0f));
-        float g = 0.5f * cst::erfcx_fast[5];
+        float g = 0.5f * cst::erfcx_fast[4];
 #pragma unroll
-        for (int k = 4; k >= 0; --k) g = fmaf(g, w, 0.5f * cst::erfcx_fast[k]);
+        for (int k = 3; k >= 0; --k) g = fmaf(g, w, 0.5f * cst::erfcx_fast[k]);
         float E = hw_exp2((x * x) * (-0.5f * kLog2e));            // exp(-z^2)
         u = (med3(x, -FLT_MAX, FLT_MAX) * (g * w)) * E;
     }
