@@ -91,7 +91,9 @@ __device__ __forceinline__ float act_fast(float x)
         float E = hw_exp2((x * x) * (-0.5f * kLog2e));            // exp(-z^2)
         u = (med3(x, -FLT_MAX, FLT_MAX) * (g * w)) * E;
     }
-    return med3(x, -0.0f, INFINITY) - fabsf(u);      // max(x, -0) in one instruction; a NaN x comes through u
+    // max(x, -0) as the median of (x, -0, |x|): one instruction (a median against the constant +inf is
+    // rewritten by the compiler into a maximum preceded by a canonicalising v_max x, x).  A NaN x comes through u.
+    return med3(x, -0.0f, fabsf(x)) - fabsf(u);
 }
 
 // ---------------------------------------------------------------------------
