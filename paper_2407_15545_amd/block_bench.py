@@ -4,7 +4,7 @@
 
 For each architecture block the forward + backward time of one training step
 is measured with torch's activation, with the InvAct layer and with the
-precision-bit InvAct layer in its place:
+precision-bit InvAct layer in its place (the variants take turns, group by group):
 
   plain        the nonlinearity alone on 2^25 elements (the paper's size), eagerly and replayed from a
                HIP graph (an MI355X needs ~60 us for this size, about what the Python call path of
@@ -74,10 +74,8 @@ class GeGlu(torch.nn.Module):
         return self.act(self.gate(x)) * self.up(x)
 
 
-def time_block(module, x, iters, groups=5, graph=False):
-    """Median over groups of the mean forward + backward time (ms) of `iters` consecutive steps.
-
-    graph=True: the step is captured once into a HIP graph and the replays are timed."""
+def prepare(module, x, graph=False):
+    """A callable that runs one forward + backward step of `module` (graph=True: replays a HIP graph of it)."""
     def step():
         y = module(x)
         y.backward(grad)
@@ -102,16 +100,28 @@ def time_block(module, x, iters, groups=5, graph=False):
     for _ in range(3):
         step()
     torch.cuda.synchronize()
-    times = []
+    return step
+
+
+def time_steps(steps, iters, groups=5):
+    """Median over groups of the mean time (ms) of `iters` consecutive calls, for every entry of the dict
+    `steps`; the entries take turns within each group, so that clock drift hits all of them alike."""
+    times = {k: [] for k in steps}
     for _ in range(groups):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(iters):
-            step()
-        e1.record()
-        torch.cuda.synchronize()
-        times.append(e0.elapsed_time(e1) / iters)
-    return statistics.median(times)
+        for k, step in steps.items():
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(iters):
+                step()
+            e1.record()
+            torch.cuda.synchronize()
+            times[k].append(e0.elapsed_time(e1) / iters)
+    return {k: statistics.median(v) for k, v in times.items()}
+
+
+def time_block(module, x, iters, groups=5, graph=False):
+    """Forward + backward time (ms) of one module alone."""
+    return time_steps({"m": prepare(module, x, graph)}, iters, groups)["m"]
 
 
 def main():
@@ -146,17 +156,16 @@ def main():
                 continue
             torch.manual_seed(0)
             x = torch.randn(*shape, device="cuda", dtype=torch.float32).to(td).requires_grad_(True)
-            res = {}
+            modules = {}
             for col, make in acts.items():
                 torch.manual_seed(1)
-                module = cls(make()).to(device="cuda", dtype=td)
-                res[col] = time_block(module, x, args.iters, graph=name.endswith("graph"))
-                del module
+                modules[col] = cls(make()).to(device="cuda", dtype=td)
             if cls is GeGlu:
                 torch.manual_seed(1)
-                module = GeGlu(glu=invact_nn.InvActGLU(kind)).to(device="cuda", dtype=td)
-                res["fused"] = time_block(module, x, args.iters)
-                del module
+                modules["fused"] = GeGlu(glu=invact_nn.InvActGLU(kind)).to(device="cuda", dtype=td)
+            steps = {col: prepare(m, x, graph=name.endswith("graph")) for col, m in modules.items()}
+            res = time_steps(steps, args.iters)
+            del steps, modules
             base = res["torch"]
             cell = lambda k: f"{res[k]:8.3f} ({100 * (res[k] / base - 1):+6.2f}%)" if k in res else ""
             print(f"{name:26s} {dt:5s} {base:9.3f} {cell('invact'):>18s} {cell('pbit'):>18s} {cell('fused'):>18s}", flush=True)

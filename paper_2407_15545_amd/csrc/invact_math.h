@@ -208,7 +208,7 @@ __device__ __forceinline__ QParts q_parts(float y, bool left)
         const auto& L = cst::silu_left;
         const auto& R = cst::silu_right;
         (void)left;
-        float yc = med3(y, -INFINITY, 64.0f);        // min(y, 64) in one instruction
+        float yc = med3(y, 64.0f, -fabsf(y));        // min(y, 64) as a median the compiler leaves alone (cf. act_fast)
         float yt = med3(y - fT, 0.0f, 64.0f);
         float sq = hw_sqrt(yt);
         // Eq. (8) as 1 + h (1 - y), h = (c0 + r) E
