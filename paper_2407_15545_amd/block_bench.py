@@ -148,6 +148,7 @@ def main():
         "Transformer MLP block": (Mlp, (BATCH, DIM)),
         "GeGLU": (GeGlu, (BATCH, DIM)),
     }
+    print(f"layers wired through {invact_nn.wiring()}", flush=True)
     print(f"{'block':26s} {'dtype':5s} {'torch ms':>9s} {'InvAct ms':>18s} {'precision-bit ms':>18s} {'InvAct fused ms':>18s}", flush=True)
     for dt in args.dtypes:
         td = {"bf16": torch.bfloat16, "fp32": torch.float32}[dt]

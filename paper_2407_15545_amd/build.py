@@ -33,6 +33,27 @@ def build(force=True, verbose=False, extra=(), out=LIB):
     return LIB
 
 
+TORCH_EXT_SRC = os.path.join(HERE, "csrc", "invact_torch.cpp")
+TORCH_EXT = os.path.join(HERE, "libinvact_torch.so")
+
+
+def build_torch_extension(verbose=False):
+    """Compile the C++ autograd wiring of the layers (host code only) against libtorch and libinvact.so."""
+    import torch
+    tdir = os.path.dirname(torch.__file__)
+    cxx = os.environ.get("CXX", "g++")
+    cmd = [cxx, "-O2", "-std=c++17", "-fPIC", "-shared", "-D__HIP_PLATFORM_AMD__=1", "-DUSE_ROCM=1",
+           f"-D_GLIBCXX_USE_CXX11_ABI={int(torch._C._GLIBCXX_USE_CXX11_ABI)}",
+           f"-I{tdir}/include", f"-I{tdir}/include/torch/csrc/api/include", "-I/opt/rocm/include",
+           "-o", TORCH_EXT, TORCH_EXT_SRC,
+           f"-L{tdir}/lib", "-ltorch", "-ltorch_cpu", "-lc10", "-lc10_hip", "-ltorch_hip",
+           f"-L{HERE}", "-linvact", "-Wl,-rpath,$ORIGIN", f"-Wl,-rpath,{tdir}/lib"]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    return TORCH_EXT
+
+
 TOOLS = {"membench": "-O3", "unit_accuracy": "-O2", "unit_rates": "-O3"}
 
 
@@ -62,3 +83,4 @@ if __name__ == "__main__":
     else:
         print(build(force=True, verbose=True, extra=argv))
         print(*build_tools(verbose=True), sep="\n")
+        print(build_torch_extension(verbose=True))

@@ -8,10 +8,47 @@ layer's OUTPUT plus the packed 1-bit mask instead of its input.  The output is
 the tensor the next layer saves anyway, so between the two layers one tensor is
 kept instead of two.  There is no CPU or eager fallback: tensors must live on
 the GPU and be float32 or bfloat16.
+
+Two wirings of the same kernels: the autograd functions below (Python), and the
+same functions written in C++ (csrc/invact_torch.cpp -> libinvact_torch.so, torch
+operators invact::act / act_pbit / glu), which are used when that library is
+built: two Python autograd hops cost more than the two kernels of a 2^25-element
+layer take on an MI355X.  INVACT_NN=python selects the Python wiring.
 """
+import os
+
 import torch
 
 from . import binding as B
+
+_TORCH_EXT = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libinvact_torch.so")
+_ops = None
+if os.environ.get("INVACT_NN", "") != "python" and os.path.exists(_TORCH_EXT):
+    B.lib()                                   # the kernels' library first: the extension links against it
+    torch.ops.load_library(_TORCH_EXT)
+    _ops = torch.ops.invact
+
+
+def wiring():
+    """'c++' if the layers go through libinvact_torch.so, 'python' if through the autograd functions here."""
+    return "python" if _ops is None else "c++"
+
+
+def set_wiring(name):
+    """Switch between the two wirings ('c++' needs libinvact_torch.so).  Returns the previous one."""
+    global _ops
+    previous = wiring()
+    if name == "python":
+        _ops = None
+    elif name == "c++":
+        if not os.path.exists(_TORCH_EXT):
+            raise RuntimeError(f"{_TORCH_EXT} is missing: build it with `python -m paper_2407_15545_amd.build`")
+        B.lib()
+        torch.ops.load_library(_TORCH_EXT)
+        _ops = torch.ops.invact
+    else:
+        raise ValueError("wiring must be 'c++' or 'python'")
+    return previous
 
 
 class _InvAct(torch.autograd.Function):
@@ -60,11 +97,15 @@ class _InvActGLU(torch.autograd.Function):
 
 def invact(x, kind="gelu_erf", precision_bit=False):
     """y = f(x) with the inverted-activation backward."""
+    if _ops is not None:
+        return (_ops.act_pbit if precision_bit else _ops.act)(x, B.KINDS[kind])
     return (_InvActPrecisionBit if precision_bit else _InvAct).apply(x, kind)
 
 
 def invact_glu(gate, up, kind="silu"):
     """h = f(gate) * up with the inverted-activation backward (SwiGLU for kind='silu', GeGLU for the GELUs)."""
+    if _ops is not None:
+        return _ops.glu(gate, up, B.KINDS[kind])
     return _InvActGLU.apply(gate, up, kind)
 
 

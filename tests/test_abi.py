@@ -100,3 +100,20 @@ def test_binding_raises_with_the_library_message():
     with pytest.raises(B.InvactError) as e:
         B._check(ERR_ALIGN)
     assert "aligned" in str(e.value) and e.value.status == ERR_ALIGN
+
+
+def test_torch_extension_loads_and_refuses_cpu_tensors():
+    """The C++ autograd wiring of the layers: the operators exist, and there is no CPU path behind them."""
+    import torch
+    from paper_2407_15545_amd import nn
+    previous = nn.set_wiring("c++")
+    try:
+        assert nn.wiring() == "c++"
+        for name in ("act", "act_pbit", "glu"):
+            assert hasattr(torch.ops.invact, name)
+        with pytest.raises(RuntimeError, match="GPU tensors"):
+            nn.invact(torch.randn(8), "gelu_erf")
+        with pytest.raises(RuntimeError, match="float32 and bfloat16|GPU tensors"):
+            nn.invact_glu(torch.randn(8), torch.randn(8), "silu")
+    finally:
+        nn.set_wiring(previous)

@@ -11,6 +11,14 @@ from paper_2407_15545_amd import nn as inv
 pytestmark = pytest.mark.gpu
 
 
+@pytest.fixture(autouse=True, params=["c++", "python"])
+def wiring(request):
+    """Every test runs through both wirings of the layers (C++ operators and Python autograd functions)."""
+    previous = inv.set_wiring(request.param)
+    yield request.param
+    inv.set_wiring(previous)
+
+
 REFS = {"gelu_erf": lambda x: F.gelu(x), "gelu_tanh": lambda x: F.gelu(x, approximate="tanh"), "silu": F.silu}
 
 
