@@ -25,8 +25,12 @@ _TORCH_EXT = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libinvact
 _ops = None
 if os.environ.get("INVACT_NN", "") != "python" and os.path.exists(_TORCH_EXT):
     B.lib()                                   # the kernels' library first: the extension links against it
-    torch.ops.load_library(_TORCH_EXT)
-    _ops = torch.ops.invact
+    try:
+        torch.ops.load_library(_TORCH_EXT)
+        _ops = torch.ops.invact
+    except OSError as e:                      # built against another torch: same kernels through the Python wiring
+        import warnings
+        warnings.warn(f"{_TORCH_EXT} does not load ({e}); using the Python autograd wiring")
 
 
 def wiring():
