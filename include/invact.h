@@ -127,6 +127,25 @@ int invact_pbit_bwd(int kind, int dtype, const void* y, const void* grad_y, void
                     size_t n, hipStream_t stream);
 
 /*
+ * Sign-bit variant (Section 3.3, "Sign-bit Inverted Activation", and its
+ * listing): no mask tensor and no change to the forward's values.  f is
+ * bounded below by C = f(T), so f(x) - C is never negative and its sign bit is
+ * free to carry the indicator.  The saved tensor is not the layer's output:
+ * its consumer (a GEMM prologue in the paper's listing; invact_sbit_decode
+ * here) first rebuilds |y_tagged| + C.
+ *   forward:  y_tagged[i] = max(f(x[i]) - C, 0) rounded to dtype, sign bit := (x[i] < T)
+ *   decode:   y[i] = |y_tagged[i]| + C rounded to dtype
+ *   backward: s_i = sign bit of y_tagged[i];  y_i = |y_tagged[i]| + C formed in binary32;
+ *             grad_x[i] = grad_y[i] * q(y_i, s_i)
+ * C is the binary32-rounded minimum of the kind.  n elements each; y_tagged == x,
+ * y == y_tagged and grad_x == grad_y may alias.
+ */
+int invact_sbit_fwd(int kind, int dtype, const void* x, void* y_tagged, size_t n, hipStream_t stream);
+int invact_sbit_decode(int kind, int dtype, const void* y_tagged, void* y, size_t n, hipStream_t stream);
+int invact_sbit_bwd(int kind, int dtype, const void* y_tagged, const void* grad_y, void* grad_x,
+                    size_t n, hipStream_t stream);
+
+/*
  * Launch tuning (process-wide, for benchmarking; results are bit-identical
  * whatever is set).  By default a workgroup is one wavefront that handles one
  * tile and retires, and every entry point caps the number of such workgroups

@@ -71,6 +71,9 @@ def load(path=None):
         "oracle_read_lsb": (c_int, [c_int, c_dbl]),
         "oracle_pbit_fwd": (None, [c_int, c_int, _dbl_p, _dbl_p, _dbl_p, c_size]),
         "oracle_pbit_bwd": (None, [c_int, c_int, _dbl_p, _dbl_p, _dbl_p, c_size]),
+        "oracle_sbit_fwd": (None, [c_int, c_int, _dbl_p, _dbl_p, _dbl_p, c_size]),
+        "oracle_sbit_decode": (None, [c_int, c_int, _dbl_p, _dbl_p, _dbl_p, c_size]),
+        "oracle_sbit_bwd": (None, [c_int, _dbl_p, _dbl_p, _dbl_p, c_size]),
         "oracle_num_threads": (c_int, []),
     }
     for name, (res, args) in protos.items():
@@ -237,6 +240,31 @@ def pbit_bwd(kind, dtype, y, grad_y):
     assert y.size == g.size
     gx = np.empty_like(y)
     lib().oracle_pbit_bwd(_kind(kind), _dtype(dtype), y, g, gx, y.size)
+    return gx
+
+
+def sbit_fwd(kind, dtype, x):
+    """Sign-bit forward -> (f(x) - C exact, the same rounded to dtype with its sign bit set to s)"""
+    x = _f64(x)
+    ve = np.empty_like(x); yt = np.empty_like(x)
+    lib().oracle_sbit_fwd(_kind(kind), _dtype(dtype), x, ve, yt, x.size)
+    return ve, yt
+
+
+def sbit_decode(kind, dtype, y_tagged):
+    """|Y| + C -> (exact, rounded to dtype)"""
+    yt = _f64(y_tagged)
+    ye = np.empty_like(yt); ys = np.empty_like(yt)
+    lib().oracle_sbit_decode(_kind(kind), _dtype(dtype), yt, ye, ys, yt.size)
+    return ye, ys
+
+
+def sbit_bwd(kind, y_tagged, grad_y):
+    """Sign-bit backward -> grad_x (unrounded double); s is the sign bit of the saved tensor"""
+    yt = _f64(y_tagged); g = _f64(grad_y)
+    assert yt.size == g.size
+    gx = np.empty_like(yt)
+    lib().oracle_sbit_bwd(_kind(kind), yt, g, gx, yt.size)
     return gx
 
 

@@ -14,6 +14,7 @@
  *   forward / backward of the layer                 Listing "forward-backward" (Algorithm 1)
  *   SwiGLU / GeGLU gated variants                   Experiments, "GeGLU" block; Limitations
  *   precision-bit variant                           Method, "Precision Bit Inverted Activation" and its listing
+ *   sign-bit variant                                Method, "Sign-bit Inverted Activation" and its listing
  *
  * Pin status.  O1, O2, O3 are pinned by identities, library routines and brute
  * force (tests/test_oracle_*.py).  O4 is "parity unpinned": the paper prints
@@ -39,6 +40,10 @@
  *   - Eq. (8), (1 + h)(1 - y) + y, is evaluated in the algebraically equal
  *     form 1 + h (1 - y): as printed it cancels to 0 for y > 2^53 even in
  *     double.
+ *   - Sign-bit variant: C is the binary32-rounded f(T); f(x) - C is clamped
+ *     at zero, rounded once to the storage dtype, and the sign bit is set on
+ *     the stored pattern; the consumer's Y + C is one binary32 addition, and
+ *     the backward evaluates q there.
  */
 #include <math.h>
 #include <stddef.h>
@@ -522,6 +527,55 @@ void oracle_pbit_bwd(int kind, int dtype, const double *y, const double *grad_y,
 #pragma omp parallel for schedule(static)
     for (size_t i = 0; i < n; ++i)
         grad_x[i] = grad_y[i] * q_with(&c, kind, y[i], oracle_read_lsb(dtype, y[i]));
+}
+
+/* ------------------------------------------------------------------ */
+/* Sign-bit variant (Section 3.3, "Sign-bit Inverted Activation", and  */
+/* its listing)                                                        */
+/* ------------------------------------------------------------------ */
+
+/* Forward: S = X < T; Y = f(X) - C with C = min f = f(T) (here the binary32-
+ * rounded f(T), like every constant), so Y >= 0 up to that rounding (clamp0
+ * takes care of the rest); Y is rounded to the storage dtype and its sign bit
+ * is set to S.  The tagged Y is what the layer saves; what it hands to the
+ * next layer is Y + C (oracle_sbit_decode). */
+void oracle_sbit_fwd(int kind, int dtype, const double *x, double *v_exact, double *y_tagged, size_t n)
+{
+    init_consts();
+    double T = T_f32[kind], C = fT_f32[kind];
+#pragma omp parallel for schedule(static)
+    for (size_t i = 0; i < n; ++i) {
+        v_exact[i] = clamp0(oracle_f_scalar(kind, x[i]) - C);
+        double mag = oracle_round_scalar(dtype, v_exact[i]);
+        y_tagged[i] = (x[i] < T) ? -fabs(mag) : fabs(mag);          /* sign bit := S (a NaN keeps S = 0) */
+    }
+}
+
+/* What the consumer of the saved tensor computes first: S = sign bit, Y = |Y| + C. */
+void oracle_sbit_decode(int kind, int dtype, const double *y_tagged, double *y_exact, double *y_stored, size_t n)
+{
+    init_consts();
+    double C = fT_f32[kind];
+#pragma omp parallel for schedule(static)
+    for (size_t i = 0; i < n; ++i) {
+        y_exact[i]  = fabs(y_tagged[i]) + C;                         /* exact in double */
+        y_stored[i] = oracle_round_scalar(dtype, y_exact[i]);
+    }
+}
+
+/* Backward: S = sign bit of the saved Y; Y + C formed in binary32 (one rounding:
+ * the working precision of the kernels' registers); dX = dY * q(Y + C, S). */
+void oracle_sbit_bwd(int kind, const double *y_tagged, const double *grad_y, double *grad_x, size_t n)
+{
+    init_consts();
+    coeff_set c; default_coeffs(&c);
+    double C = fT_f32[kind];
+#pragma omp parallel for schedule(static)
+    for (size_t i = 0; i < n; ++i) {
+        int s = signbit(y_tagged[i]) != 0 && !isnan(y_tagged[i]);
+        double y = oracle_round_scalar(DTYPE_FP32, fabs(y_tagged[i]) + C);
+        grad_x[i] = grad_y[i] * q_with(&c, kind, y, s);
+    }
 }
 
 int oracle_num_threads(void)

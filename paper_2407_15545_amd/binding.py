@@ -30,6 +30,9 @@ _PROTOTYPES = {
     "geglu_invact_bwd": (_int, [_int, _int, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "invact_pbit_fwd": (_int, [_int, _int, _vp, _vp, _sz, _vp]),
     "invact_pbit_bwd": (_int, [_int, _int, _vp, _vp, _vp, _sz, _vp]),
+    "invact_sbit_fwd": (_int, [_int, _int, _vp, _vp, _sz, _vp]),
+    "invact_sbit_decode": (_int, [_int, _int, _vp, _vp, _sz, _vp]),
+    "invact_sbit_bwd": (_int, [_int, _int, _vp, _vp, _vp, _sz, _vp]),
     "swiglu_invact_fwd": (_int, [_int, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "swiglu_invact_bwd": (_int, [_int, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
 }
@@ -189,6 +192,34 @@ def invact_pbit_bwd(kind, y, grad_y, grad_x=None, stream=None):
     dt, n = _tensors(y, grad_y, grad_x)
     with _on_device(y.device):
         _check(lib().invact_pbit_bwd(_kind(kind), dt, y.data_ptr(), grad_y.data_ptr(), grad_x.data_ptr(), n,
+                                     _stream(stream)))
+    return grad_x
+
+
+def invact_sbit_fwd(kind, x, y_tagged=None, stream=None):
+    """Sign-bit forward: f(x) - min f with the indicator in the sign bit.  Returns the tensor to save."""
+    y_tagged = torch.empty_like(x) if y_tagged is None else y_tagged
+    dt, n = _tensors(x, y_tagged)
+    with _on_device(x.device):
+        _check(lib().invact_sbit_fwd(_kind(kind), dt, x.data_ptr(), y_tagged.data_ptr(), n, _stream(stream)))
+    return y_tagged
+
+
+def invact_sbit_decode(kind, y_tagged, y=None, stream=None):
+    """|y_tagged| + min f: the activation, rebuilt from the saved tensor.  Returns y."""
+    y = torch.empty_like(y_tagged) if y is None else y
+    dt, n = _tensors(y_tagged, y)
+    with _on_device(y.device):
+        _check(lib().invact_sbit_decode(_kind(kind), dt, y_tagged.data_ptr(), y.data_ptr(), n, _stream(stream)))
+    return y
+
+
+def invact_sbit_bwd(kind, y_tagged, grad_y, grad_x=None, stream=None):
+    """Sign-bit backward: grad_x = grad_y * q(|y_tagged| + min f, sign bit).  Returns grad_x."""
+    grad_x = torch.empty_like(grad_y) if grad_x is None else grad_x
+    dt, n = _tensors(y_tagged, grad_y, grad_x)
+    with _on_device(y_tagged.device):
+        _check(lib().invact_sbit_bwd(_kind(kind), dt, y_tagged.data_ptr(), grad_y.data_ptr(), grad_x.data_ptr(), n,
                                      _stream(stream)))
     return grad_x
 

@@ -425,6 +425,80 @@ struct PbitBwdOp {                   // s = bit 0 of y; grad_x = grad_y * q(y, s
     static constexpr Shape kShape = pick<DT>({2, 8}, {1, 32});   // {tiles, resident cap}: binary32, bfloat16
 };
 
+// Sign-bit variant: no mask tensor and an exact forward; the saved tensor is f(x) - min f, which is
+// never negative, with the indicator in its sign bit.  Whoever consumes it adds the minimum back.
+template <int KIND, int DT>
+struct SbitFwdOp {                   // y_tagged = +-(f(x) - C), sign bit := [x < T]
+    using S = Storage<DT>;
+    const void* x; void* yt;
+    struct In { typename S::Raw x; };
+    __device__ __forceinline__ void load(In& in, size_t c) const { in.x = S::load(x, c); }
+    __device__ __forceinline__ void run(const In& in, size_t c) const
+    {
+        float v[8]; S::unpack(in.x, v);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = act_minus_min_signed<KIND, S::kPrec>(v[j]);
+        S::store(yt, c, v);
+    }
+    __device__ __forceinline__ bool scalar(size_t i, bool) const
+    {
+        S::store1(yt, i, act_minus_min_signed<KIND, S::kPrec>(S::load1(x, i)));
+        return false;
+    }
+    static constexpr int kMask = MASK_NONE;
+    static constexpr Shape kShape = pick<DT>({2, 32}, {1, 32});   // {tiles, resident cap}: binary32, bfloat16
+};
+
+template <int KIND, int DT>
+struct SbitDecodeOp {                // y = |y_tagged| + C
+    using S = Storage<DT>;
+    const void* yt; void* y;
+    struct In { typename S::Raw y; };
+    __device__ __forceinline__ void load(In& in, size_t c) const { in.y = S::load(yt, c); }
+    __device__ __forceinline__ void run(const In& in, size_t c) const
+    {
+        float v[8]; S::unpack(in.y, v);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = fabsf(v[j]) + KindConst<KIND>::fT;
+        S::store(y, c, v);
+    }
+    __device__ __forceinline__ bool scalar(size_t i, bool) const
+    {
+        S::store1(y, i, fabsf(S::load1(yt, i)) + KindConst<KIND>::fT);
+        return false;
+    }
+    static constexpr int kMask = MASK_NONE;
+    static constexpr Shape kShape = pick<DT>({2, 32}, {1, 32});   // {tiles, resident cap}: binary32, bfloat16
+};
+
+template <int KIND, int DT>
+struct SbitBwdOp {                   // s = sign bit of y_tagged; grad_x = grad_y * q(|y_tagged| + C, s)
+    using S = Storage<DT>;
+    const void* yt; const void* gy; void* gx;
+    struct In { typename S::Raw y, g; };
+    __device__ __forceinline__ void load(In& in, size_t c) const { in.y = S::load(yt, c); in.g = S::load(gy, c); }
+    static __device__ __forceinline__ float one(float g, float t)
+    {
+        return times_q<KIND, S::kPrec>(g, fabsf(t) + KindConst<KIND>::fT, (__float_as_uint(t) >> 31) != 0);
+    }
+    __device__ __forceinline__ void run(const In& in, size_t c) const
+    {
+        float a[8], g[8];
+        S::unpack(in.y, a);
+        S::unpack(in.g, g);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) g[j] = one(g[j], a[j]);
+        S::store(gx, c, g);
+    }
+    __device__ __forceinline__ bool scalar(size_t i, bool) const
+    {
+        S::store1(gx, i, one(S::load1(gy, i), S::load1(yt, i)));
+        return false;
+    }
+    static constexpr int kMask = MASK_NONE;
+    static constexpr Shape kShape = pick<DT>({2, 8}, {1, 32});   // {tiles, resident cap}: binary32, bfloat16
+};
+
 // ---------------------------------------------------------------------------
 // Skeleton
 // ---------------------------------------------------------------------------
@@ -697,6 +771,37 @@ int invact_pbit_bwd(int kind, int dtype, const void* y, const void* grad_y, void
     if (int e = check_data({y, grad_y, grad_x})) return e;
     return dispatch(kind, dtype, [&](auto K, auto D) {
         return launch(PbitBwdOp<K.value, D.value>{y, grad_y, grad_x}, n, stream);
+    });
+}
+
+int invact_sbit_fwd(int kind, int dtype, const void* x, void* y_tagged, size_t n, hipStream_t stream)
+{
+    if (int e = check_common(kind, dtype, n)) return e;
+    if (n == 0) return INVACT_OK;
+    if (int e = check_data({x, y_tagged})) return e;
+    return dispatch(kind, dtype, [&](auto K, auto D) {
+        return launch(SbitFwdOp<K.value, D.value>{x, y_tagged}, n, stream);
+    });
+}
+
+int invact_sbit_decode(int kind, int dtype, const void* y_tagged, void* y, size_t n, hipStream_t stream)
+{
+    if (int e = check_common(kind, dtype, n)) return e;
+    if (n == 0) return INVACT_OK;
+    if (int e = check_data({y_tagged, y})) return e;
+    return dispatch(kind, dtype, [&](auto K, auto D) {
+        return launch(SbitDecodeOp<K.value, D.value>{y_tagged, y}, n, stream);
+    });
+}
+
+int invact_sbit_bwd(int kind, int dtype, const void* y_tagged, const void* grad_y, void* grad_x, size_t n,
+                    hipStream_t stream)
+{
+    if (int e = check_common(kind, dtype, n)) return e;
+    if (n == 0) return INVACT_OK;
+    if (int e = check_data({y_tagged, grad_y, grad_x})) return e;
+    return dispatch(kind, dtype, [&](auto K, auto D) {
+        return launch(SbitBwdOp<K.value, D.value>{y_tagged, grad_y, grad_x}, n, stream);
     });
 }
 

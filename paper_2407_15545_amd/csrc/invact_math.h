@@ -176,6 +176,24 @@ __device__ __forceinline__ void act_times(float gate, float up, float& a, float&
     }
 }
 
+// Sign-bit variant (Section 3.3): f(x) - C with C = f(T) the minimum of f, clamped at 0 (the
+// difference is negative only by the rounding of C), rounded once to binary32, with its sign bit
+// set to the indicator [x < T].  A NaN x gives a NaN.
+template <int KIND, int PREC>
+__device__ __forceinline__ float act_minus_min_signed(float x)
+{
+    constexpr float C = KindConst<KIND>::fT;
+    float v;
+    if constexpr (PREC == FAST) {
+        float d = act_fast<KIND>(x) - C;
+        v = (d < 0.0f) ? 0.0f : d;                      // keeps a NaN
+    } else {
+        double d = act_precise<KIND>(x) - (double)C;
+        v = nan_through(x, (float)((d < 0.0) ? 0.0 : d));
+    }
+    return (x < KindConst<KIND>::T) ? -v : v;
+}
+
 // ---------------------------------------------------------------------------
 // Backward: q(y, s) ~ f'(f^-1(y)), Eqs. (5)-(8)
 // ---------------------------------------------------------------------------

@@ -99,6 +99,31 @@ class _InvActGLU(torch.autograd.Function):
         return grad_gate.view_as(grad_h), grad_up.view_as(grad_h), None
 
 
+class _SignBitActLinear(torch.autograd.Function):
+    """Activation followed by a linear layer, sign-bit variant (Section 3.3 and its listing): the only
+    saved activation is f(x) - min f with the indicator in its sign bit; f(x) itself is rebuilt when
+    the matrix products need it and dropped again."""
+
+    @staticmethod
+    def forward(ctx, x, weight, bias, kind):
+        y_tagged = B.invact_sbit_fwd(kind, x.contiguous())
+        out = torch.nn.functional.linear(B.invact_sbit_decode(kind, y_tagged).view_as(x), weight, bias)
+        ctx.kind, ctx.has_bias = kind, bias is not None
+        ctx.save_for_backward(y_tagged, weight)
+        return out
+
+    @staticmethod
+    def backward(ctx, grad_out):
+        y_tagged, weight = ctx.saved_tensors
+        g2 = grad_out.reshape(-1, grad_out.shape[-1])
+        y2 = B.invact_sbit_decode(ctx.kind, y_tagged).view(-1, weight.shape[1])
+        grad_w = g2.t().mm(y2)
+        grad_b = g2.sum(0) if ctx.has_bias else None
+        grad_y = g2.mm(weight).contiguous()
+        grad_x = B.invact_sbit_bwd(ctx.kind, y_tagged.view(-1), grad_y.view(-1)).view(y_tagged.shape)
+        return grad_x, grad_w, grad_b, None
+
+
 def invact(x, kind="gelu_erf", precision_bit=False):
     """y = f(x) with the inverted-activation backward."""
     if _ops is not None:
@@ -154,6 +179,20 @@ class InvActGLU(torch.nn.Module):
 
     def forward(self, gate, up):
         return invact_glu(gate, up, self.kind)
+
+
+class SignBitActLinear(torch.nn.Linear):
+    """linear(f(x)): an activation and the linear layer after it as ONE layer, the form the sign-bit variant
+    needs (the saved tensor is not the activation, so the consumer has to be part of the layer)."""
+
+    def __init__(self, in_features, out_features, bias=True, kind="gelu_erf", device=None, dtype=None):
+        super().__init__(in_features, out_features, bias=bias, device=device, dtype=dtype)
+        if kind not in B.KINDS:
+            raise ValueError(f"kind must be one of {sorted(B.KINDS)}")
+        self.kind = kind
+
+    def forward(self, x):
+        return _SignBitActLinear.apply(x, self.weight, self.bias, self.kind)
 
 
 def saved_activation_bytes(fn):

@@ -21,6 +21,7 @@ BYTES = {  # algorithmic bytes per element: (fp32, bf16)
     "invact_fwd": (8.125, 4.125), "invact_bwd": (12.125, 6.125),
     "geglu_invact_fwd": (16.125, 8.125), "geglu_invact_bwd": (20.125, 10.125),
     "invact_pbit_fwd": (8.0, 4.0), "invact_pbit_bwd": (12.0, 6.0),
+    "invact_sbit_fwd": (8.0, 4.0), "invact_sbit_decode": (8.0, 4.0), "invact_sbit_bwd": (12.0, 6.0),
 }
 
 
@@ -98,7 +99,11 @@ def main():
                     B.invact_fwd(kind, a, y=o1, mask=mask)          # a valid (y, mask) pair for the backward
                     y_saved = o1.clone()
                     y_tagged = B.invact_pbit_fwd(kind, a)
+                    y_signed = B.invact_sbit_fwd(kind, a)
                     calls = {
+                        "invact_sbit_fwd": lambda: B.invact_sbit_fwd(kind, a, y_tagged=o1),
+                        "invact_sbit_decode": lambda: B.invact_sbit_decode(kind, y_signed, y=o1),
+                        "invact_sbit_bwd": lambda: B.invact_sbit_bwd(kind, y_signed, b, grad_x=o1),
                         "invact_pbit_fwd": lambda: B.invact_pbit_fwd(kind, a, y=o1),
                         "invact_pbit_bwd": lambda: B.invact_pbit_bwd(kind, y_tagged, b, grad_x=o1),
                         "invact_fwd": lambda: B.invact_fwd(kind, a, y=o1, mask=mask),

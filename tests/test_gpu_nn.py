@@ -121,3 +121,28 @@ def test_block_bench_blocks_match_torch_and_time():
     xs = torch.randn(1 << 16, device="cuda", dtype=torch.bfloat16, requires_grad=True)
     for graph in (False, True):
         assert BB.time_block(BB.Plain(inv.InvActGELU()), xs, iters=3, groups=2, graph=graph) > 0
+
+
+@pytest.mark.parametrize("kind", ["gelu_erf", "silu"])
+def test_sign_bit_act_linear_matches_torch_and_saves_one_tensor(kind, wiring):
+    if wiring != "python":
+        pytest.skip("the sign-bit layer has one wiring")
+    torch.manual_seed(3)
+    tokens, d_in, d_out = 512, 1024, 256
+    x = torch.randn(tokens, d_in, device="cuda", dtype=torch.bfloat16, requires_grad=True)
+    layer = inv.SignBitActLinear(d_in, d_out, kind=kind, device="cuda", dtype=torch.bfloat16)
+    PT.say(f"nn sign-bit act + linear {kind}")
+    out = layer(x)
+    ref = F.linear(REFS[kind](x), layer.weight, layer.bias)
+    assert torch.allclose(out.float(), ref.float(), rtol=3e-2, atol=3e-2)
+    g = torch.randn_like(out)
+    gx, gw, gb = torch.autograd.grad(out, (x, layer.weight, layer.bias), g)
+    rx, rw, rb = torch.autograd.grad(ref, (x, layer.weight, layer.bias), g)
+    for a, b in ((gx, rx), (gw, rw), (gb, rb)):
+        assert (a.float() - b.float()).norm() / b.float().norm() < 3e-2
+    # saved: the tagged tensor (same size as x) and the weight; torch keeps x, f(x) and the weight
+    ours = inv.saved_activation_bytes(lambda: layer(x))[0]
+    base = inv.saved_activation_bytes(lambda: F.linear(REFS[kind](x), layer.weight, layer.bias))[0]
+    weight_bytes = layer.weight.numel() * 2
+    assert ours - weight_bytes == x.numel() * 2
+    assert base - weight_bytes == 2 * x.numel() * 2

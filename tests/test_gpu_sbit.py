@@ -1,0 +1,158 @@
+"""GPU parity of the sign-bit variant (invact_sbit_fwd / invact_sbit_decode / invact_sbit_bwd)
+against the oracle.
+
+Forward: the sign bit of every stored pattern must equal the indicator exactly.  The magnitude is
+f(x) - C, a difference that cancels next to the minimum of f, so a bound relative to the result
+cannot hold there.  What the method needs is that the rebuilt activation |Y| + C is within 2 ulp of
+f(x), i.e. an error of 2 ulp of the storage dtype at the scale of the operands; what is asserted is
+tighter and follows the arithmetic of the two policies: 2 ulp of the storage dtype at the RESULT, or
+the working precision at the scale of the operands (max(|f(x)|, |C|)), whichever is larger -- two
+binary32 ulps for binary32 storage (binary64 inside), 2^-14 relative for bfloat16 storage (binary32
+inside, and the erf form's erfcx fit is good to 3.4e-5).  Decode: |Y| + C is one
+correctly rounded binary32 addition, so binary32 storage must match bit for bit and bfloat16 within
+the usual 2 ulp.  Backward: fed with the ORACLE's saved tensor, same tolerance as invact_bwd."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+import parity as PT
+from paper_2407_15545_amd import binding as B
+from paper_2407_15545_amd import synth
+
+pytestmark = pytest.mark.gpu
+KINDS = ["gelu_tanh", "gelu_erf", "silu"]
+DTYPES = ["fp32", "bf16"]
+SIZES = [1, 7, 63, 64, 65, 511, 513, 4096 + 8, (1 << 20) + 3]
+
+
+def sign_bits(t):
+    if t.dtype == torch.bfloat16:
+        return (t.view(torch.int16).cpu().numpy().view(np.uint16) >> 15).astype(np.uint8)
+    return (t.view(torch.int32).cpu().numpy().view(np.uint32) >> 31).astype(np.uint8)
+
+
+def inputs(n, seed, dtype):
+    x = synth.to_storage(synth.normal(n, seed, 2.0), dtype)
+    g = synth.to_storage(synth.normal(n, seed + 1, 1.0), dtype)
+    return x, g
+
+
+def magnitude_errors(gpu_tagged, v_exact, f_exact, C, dtype):
+    """|gpu| against the exact f(x) - C in units of the tolerance of the module docstring."""
+    gpu = np.abs(np.asarray(gpu_tagged, np.float64))
+    out = np.zeros(v_exact.shape)
+    nan = np.isnan(v_exact)
+    out[nan] = np.where(np.isnan(gpu[nan]), 0.0, np.inf)
+    inf = np.isinf(v_exact)
+    out[inf] = np.where(gpu[inf] == np.inf, 0.0, np.inf)
+    r = ~nan & ~inf
+    scale = np.maximum(np.abs(f_exact[r]), abs(C))
+    floor = 2.0 * PT.ulp(scale, "fp32") if dtype == "fp32" else 2.0 ** -14 * scale
+    tol = np.maximum(2.0 * PT.ulp(v_exact[r], dtype), floor)
+    out[r] = np.where(np.isfinite(gpu[r]), np.abs(gpu[r] - v_exact[r]) / tol, np.inf)
+    return out
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("kind", KINDS)
+def test_sbit_forward_decode_backward(kind, dtype):
+    C = O.fT(kind, f32=True)
+    for n in SIZES:
+        PT.say(f"invact_sbit fwd/decode/bwd {kind} {dtype} n={n}")
+        xs, gs = inputs(n, 500 + n, dtype)
+        x64, g64 = synth.storage_to_f64(xs, dtype), synth.storage_to_f64(gs, dtype)
+        ve, yt = O.sbit_fwd(kind, dtype, x64)
+        got = B.invact_sbit_fwd(kind, PT.to_device(xs, dtype))
+        torch.cuda.synchronize()
+        assert np.array_equal(sign_bits(got), O.indicator(kind, x64)), "sign bit differs from the indicator"
+        err = magnitude_errors(PT.to_f64(got), ve, O.f(kind, x64), C, dtype)
+        assert err.max() <= 1.0, (n, PT.worst(err, x64, ve, PT.to_f64(got)))
+
+        # decode and backward from the oracle's saved tensor
+        saved = PT.to_device(synth.f64_to_storage_exact(yt, dtype), dtype)
+        ye, ys = O.sbit_decode(kind, dtype, yt)
+        y = B.invact_sbit_decode(kind, saved)
+        torch.cuda.synchronize()
+        if dtype == "fp32":
+            assert np.array_equal(PT.to_f64(y), ys)
+        err = PT.forward_errors(PT.to_f64(y), ye, dtype)
+        assert err.max() <= 1.0, (n, PT.worst(err, yt, ye, PT.to_f64(y)))
+        ref = O.sbit_bwd(kind, yt, g64)
+        gx = B.invact_sbit_bwd(kind, saved, PT.to_device(gs, dtype))
+        torch.cuda.synchronize()
+        err = PT.backward_errors(PT.to_f64(gx), ref, g64, dtype)
+        assert err.max() <= 1.0, (n, PT.worst(err, yt, g64, ref, PT.to_f64(gx)))
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_sbit_every_bf16_pattern(kind):
+    C = O.fT(kind, f32=True)
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    with np.errstate(invalid="ignore"):
+        x64 = synth.storage_to_f64(bits, "bf16")
+    ve, yt = O.sbit_fwd(kind, "bf16", x64)
+    PT.say(f"invact_sbit_fwd {kind} all bf16 patterns")
+    got = B.invact_sbit_fwd(kind, PT.to_device(bits, "bf16"))
+    torch.cuda.synchronize()
+    ok = ~np.isnan(x64)
+    assert np.array_equal(sign_bits(got)[ok], O.indicator(kind, x64)[ok])
+    with np.errstate(invalid="ignore"):
+        err = magnitude_errors(PT.to_f64(got), ve, O.f(kind, x64), C, "bf16")
+    assert err.max() <= 1.0, PT.worst(err, x64, ve, PT.to_f64(got))
+    # every pattern as a saved tensor through decode and backward (grad_y = 1)
+    y_saved = x64
+    ye, _ = O.sbit_decode(kind, "bf16", y_saved)
+    y = B.invact_sbit_decode(kind, PT.to_device(bits, "bf16"))
+    torch.cuda.synchronize()
+    err = PT.forward_errors(PT.to_f64(y), ye, "bf16")
+    assert err.max() <= 1.0, PT.worst(err, y_saved, ye, PT.to_f64(y))
+    # left-branch values far outside f's range overflow in binary32 where double does not: see test_gpu_parity
+    strict = (ye <= 1.0) | ~np.signbit(y_saved) | np.isnan(y_saved)
+    ref = O.sbit_bwd(kind, y_saved, np.ones(y_saved.size))
+    gx = B.invact_sbit_bwd(kind, PT.to_device(bits, "bf16"), torch.ones(y_saved.size, dtype=torch.bfloat16, device="cuda"))
+    torch.cuda.synchronize()
+    res = PT.to_f64(gx)
+    err = PT.backward_errors(res[strict], ref[strict], np.ones(int(strict.sum())), "bf16")
+    assert err.max() <= 1.0, PT.worst(err, y_saved[strict], ref[strict], res[strict])
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_sbit_in_place(dtype):
+    n = 70001
+    xs, gs = inputs(n, 78, dtype)
+    x, g = PT.to_device(xs, dtype), PT.to_device(gs, dtype)
+    PT.say(f"invact_sbit in place {dtype}")
+    yt = B.invact_sbit_fwd("gelu_erf", x)
+    y = B.invact_sbit_decode("gelu_erf", yt)
+    gx = B.invact_sbit_bwd("gelu_erf", yt, g)
+    x2, y2, g2 = x.clone(), yt.clone(), g.clone()
+    B.invact_sbit_fwd("gelu_erf", x2, y_tagged=x2)
+    B.invact_sbit_decode("gelu_erf", y2, y=y2)
+    B.invact_sbit_bwd("gelu_erf", yt, g2, grad_x=g2)
+    torch.cuda.synchronize()
+    assert torch.equal(x2.view(torch.uint8), yt.view(torch.uint8))
+    assert torch.equal(y2.view(torch.uint8), y.view(torch.uint8))
+    assert torch.equal(g2.view(torch.uint8), gx.view(torch.uint8))
+
+
+def test_sbit_round_trip_rebuilds_the_activation_to_the_grid_of_the_stored_value():
+    """decode(fwd(x)) against f(x).  The stored f - C and the sum |Y| + C are each rounded at the scale of
+    max(|f|, |C|), so that is the accuracy of the rebuilt activation: absolute, not relative to f(x).  Where
+    |f(x)| is far below |C| (x near 0) the rebuilt value keeps few of its own digits -- a property of the
+    variant in floating point, not of this implementation; invact_fwd's y is within 2 ulp of f(x) itself."""
+    n = 1 << 18
+    for dtype in DTYPES:
+        xs, _ = inputs(n, 91, dtype)
+        x = PT.to_device(xs, dtype)
+        y_plain, _ = B.invact_fwd("silu", x)
+        y = B.invact_sbit_decode("silu", B.invact_sbit_fwd("silu", x))
+        torch.cuda.synchronize()
+        f = O.f("silu", synth.storage_to_f64(xs, dtype))
+        scale = np.maximum(np.abs(f), abs(O.fT("silu", f32=True)))
+        assert np.all(np.abs(PT.to_f64(y) - f) <= 1.5 * PT.ulp(scale, dtype))
+        assert (PT.forward_errors(PT.to_f64(y_plain), f, dtype) * 2).max() <= 2.0
+        small = np.abs(f) < 2.0 ** -6
+        worse = np.abs(PT.to_f64(y) - f)[small].max() / np.abs(PT.to_f64(y_plain) - f)[small].max()
+        PT.say(f"sign-bit round trip {dtype}: largest error where |f| < 2^-6 is {worse:.0f} x that of invact_fwd")
+        assert worse > 4

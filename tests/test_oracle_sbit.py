@@ -1,0 +1,87 @@
+"""Pins of the oracle's sign-bit variant (Section 3.3, "Sign-bit Inverted Activation", and its
+listing): the forward stores f(x) - C (C = min f, so the value is non-negative) with its sign bit
+replaced by the indicator; the consumer rebuilds |Y| + C; the backward reads the sign and evaluates
+q at |Y| + C.  Pinned by redoing the bit operations with numpy's integer views, by the round trip
+back to f(x), and by the ordinary variant (whose result it must reproduce up to the rounding of
+the stored value)."""
+import numpy as np
+import pytest
+
+import oracle as O
+from paper_2407_15545_amd import synth
+
+KINDS = ["gelu_tanh", "gelu_erf", "silu"]
+P = {"fp32": 24, "bf16": 8}
+
+
+def patterns(values, dtype):
+    st = synth.f64_to_storage_exact(values, dtype)
+    return st.view(np.uint32).copy() if dtype == "fp32" else st.astype(np.uint32)
+
+
+def sign_bit(dtype):
+    return np.uint32(0x80000000 if dtype == "fp32" else 0x8000)
+
+
+def inputs(dtype, n=50000, seed=3):
+    rng = np.random.default_rng(seed)
+    x = synth.storage_to_f64(synth.to_storage((rng.standard_normal(n) * 2.5).astype(np.float32), dtype), dtype)
+    return x
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("kind", KINDS)
+def test_forward_stores_f_minus_its_minimum_with_the_indicator_as_sign(kind, dtype):
+    x = np.concatenate([inputs(dtype), [0.0, -0.0, O.T(kind, f32=True), -30.0, 30.0, np.inf, -np.inf]])
+    C = O.fT(kind, f32=True)
+    ve, yt = O.sbit_fwd(kind, dtype, x)
+    s = O.indicator(kind, x).astype(np.uint32)
+    pat = patterns(yt, dtype)
+    assert np.array_equal((pat & sign_bit(dtype)) != 0, s.astype(bool))            # the sign carries the indicator
+    assert np.array_equal(pat & ~sign_bit(dtype), patterns(O.round_to(dtype, ve), dtype))   # the rest is RNE(f - C)
+    f = O.f(kind, x)
+    assert np.all(ve >= 0)
+    fin = np.isfinite(f)
+    assert np.array_equal(ve[fin], np.maximum(f[fin] - C, 0.0))
+    # f(T) is the minimum: the difference is negative only by the rounding of C to binary32
+    assert np.min(f[fin] - C) > -2.0 ** -25 * abs(C)
+    # -inf -> f = -0 -> stored magnitude -C, sign 1; +inf stays +inf with sign 0
+    assert yt[-1] == O.round_to(dtype, np.array([C]))[0] and yt[-2] == np.inf
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("kind", KINDS)
+def test_decode_gives_back_the_activation(kind, dtype):
+    x = inputs(dtype, seed=4)
+    C = O.fT(kind, f32=True)
+    _, yt = O.sbit_fwd(kind, dtype, x)
+    ye, ys = O.sbit_decode(kind, dtype, yt)
+    assert np.array_equal(ye, np.abs(yt) + C)
+    assert np.array_equal(ys, O.round_to(dtype, ye))
+    # |Y| + C differs from f(x) by the rounding of the stored difference: half an ulp of f - C
+    f = O.f(kind, x)
+    ulp_v = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(yt), 2.0 ** -126))) - P[dtype] + 1)
+    assert np.all(np.abs(ye - f) <= 0.5 * ulp_v + 2.0 ** -25 * abs(C))
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("kind", KINDS)
+def test_backward_reads_the_sign_and_evaluates_q_at_the_rebuilt_value(kind, dtype):
+    x = inputs(dtype, n=20000, seed=5)
+    g = np.random.default_rng(6).standard_normal(x.size)
+    C = O.fT(kind, f32=True)
+    _, yt = O.sbit_fwd(kind, dtype, x)
+    gx = O.sbit_bwd(kind, yt, g)
+    s = np.signbit(yt).astype(np.uint8)
+    assert np.array_equal(s, O.indicator(kind, x))
+    y32 = (np.abs(yt) + C).astype(np.float32).astype(np.float64)      # Y + C in binary32 registers
+    assert np.array_equal(gx, g * O.q(kind, y32, s))
+    # same gradient as the ordinary variant up to what the two stored values differ by
+    _, plain, m = O.invact_fwd(kind, dtype, x)
+    ref = O.invact_bwd(kind, plain, m, g)
+    assert np.max(np.abs(gx - ref)) <= (4e-2 if dtype == "bf16" else 1e-3) * np.max(np.abs(g))
+    # and closer to the exact derivative than the ordinary variant in bfloat16: the stored f - C keeps its
+    # relative precision next to the minimum, where f' goes like its square root
+    if dtype == "bf16":
+        exact = g * O.df(kind, x)
+        assert np.sqrt(np.mean((gx - exact) ** 2)) < np.sqrt(np.mean((ref - exact) ** 2))
