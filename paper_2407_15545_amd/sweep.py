@@ -111,9 +111,9 @@ def main():
                         "geglu_invact_fwd": lambda: B.geglu_invact_fwd(kind, a, b, act=o1, h=o2, mask=mask),
                         "geglu_invact_bwd": lambda: B.geglu_invact_bwd(kind, y_saved, b, mask, c, grad_gate=o1, grad_up=o2),
                     }
+                    shapes = [(bpc, res) for bpc in args.blocks_per_cu for res in args.resident]
                     for entry in args.entries:
-                        for bpc in args.blocks_per_cu:
-                          for res in args.resident:
+                        for bpc, res in shapes:
                             B.set_blocks_per_cu(bpc)
                             B.set_resident_blocks(res)
                             B.invact_fwd(kind, a, y=o2, mask=mask)  # restore the mask the backward reads
