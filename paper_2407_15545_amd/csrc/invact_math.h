@@ -100,17 +100,18 @@ __device__ __forceinline__ float act_fast(float x)
 // Forward, PRECISE
 // ---------------------------------------------------------------------------
 
-// 2^t for a binary64 t in [-30000, 0]:  t = n + f with n = round(t), |f| <= 1/2 (t - n is exact),
+// 2^(a b) for a binary64 product t = a b in [-30000, 0]:  t = n + f with n = round(t), |f| <= 1/2,
 // 2^f by a degree-6 polynomial in binary64 (relative error 2.6e-9: the hardware exponential's
 // 0.78 ulp of binary32 would be the largest error of the whole forward), and the scaling by 2^n
 // exact (v_ldexp_f64, no subnormal binary32 intermediate).  n comes from adding 1.5 * 2^52: the sum
 // is rounded to an integer, and since the low 32 bits of that constant's significand are zero the
-// low word of the sum is n itself in two's complement.  A NaN t gives NaN.
-__device__ __forceinline__ double exp2_neg(double t)
+// low word of the sum is n itself in two's complement.  Both uses of the product are fused
+// (fma(a, b, .)), so the product is never rounded on its own and costs no instruction.  A NaN gives NaN.
+__device__ __forceinline__ double exp2_neg(double a, double b)
 {
     constexpr double kRound = 6755399441055744.0;        // 1.5 * 2^52
-    double s = t + kRound;
-    double f = t - (s - kRound);
+    double s = fma(a, b, kRound);
+    double f = fma(a, b, kRound - s);                    // kRound - s = -n exactly
     double p = cst::exp2_precise[6];
 #pragma unroll
     for (int k = 5; k >= 0; --k) p = fma(p, f, cst::exp2_precise[k]);
@@ -131,12 +132,12 @@ __device__ __forceinline__ double act_precise(float x)
     double u;
     if constexpr (KIND == SILU) {
         double xd = (double)med3(x, -2048.0f, 2048.0f);        // beyond, the gate underflows to 0 anyway
-        double E  = exp2_neg(-fabs(xd) * kLog2eD);
+        double E  = exp2_neg(-fabs(xd), kLog2eD);
         u = xd * E * rcp_newton(1.0 + E);
     } else if constexpr (KIND == GELU_TANH) {
         constexpr double a = 2.0 * kSqrt2OverPi * kLog2eD, b = a * kGeluCubic;
         double xd = (double)med3(x, -64.0f, 64.0f);
-        double E  = exp2_neg(-fabs(xd * fma(b, xd * xd, a)));
+        double E  = exp2_neg(-fabs(xd), fma(b, xd * xd, a));     // a, b > 0
         u = xd * E * rcp_newton(1.0 + E);
     } else {
         double xd = (double)med3(x, -64.0f, 64.0f);
@@ -144,7 +145,7 @@ __device__ __forceinline__ double act_precise(float x)
         double g  = 0.5 * cst::erfcx_precise[9];
 #pragma unroll
         for (int k = 8; k >= 0; --k) g = fma(g, w, 0.5 * cst::erfcx_precise[k]);
-        double E = exp2_neg((xd * xd) * (-0.5 * kLog2eD));
+        double E = exp2_neg(xd * (-0.5 * kLog2eD), xd);
         u = xd * (g * w) * E;
     }
     return fmax((double)x, -0.0) - fabs(u);
