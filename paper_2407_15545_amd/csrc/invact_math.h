@@ -125,7 +125,8 @@ __device__ __forceinline__ double rcp_newton(double d)
     return r * fma(-d, r, 2.0);
 }
 
-// f(x) in binary64, not yet protected against a NaN x (see nan_through).
+// f(x) in binary64.  For SiLU and the tanh form the clamp of x drops a NaN and the callers put it
+// back (nan_through); in the erf form the NaN arrives through w.
 template <int KIND>
 __device__ __forceinline__ double act_precise(float x)
 {
@@ -140,8 +141,13 @@ __device__ __forceinline__ double act_precise(float x)
         double E  = exp2_neg(-fabs(xd), fma(b, xd * xd, a));     // a, b > 0
         u = xd * E * rcp_newton(1.0 + E);
     } else {
+        // w = 1 / (1 + p z): binary32 seed from the UNCLAMPED x (a NaN x thus reaches the result through w,
+        // and an infinite one gives w = 0), one Newton step in binary64 against the clamped argument.
+        // Beyond the clamp the two disagree, but there exp(-z^2) is exactly 0.
+        constexpr double pz = cst::erfcx_precise_p * kInvSqrt2;
         double xd = (double)med3(x, -64.0f, 64.0f);
-        double w  = rcp_newton(fma(cst::erfcx_precise_p * kInvSqrt2, fabs(xd), 1.0));
+        double r  = (double)hw_rcp(fmaf((float)pz, fabsf(x), 1.0f));
+        double w  = r * fma(-fma(pz, fabs(xd), 1.0), r, 2.0);
         double g  = 0.5 * cst::erfcx_precise[9];
 #pragma unroll
         for (int k = 8; k >= 0; --k) g = fma(g, w, 0.5 * cst::erfcx_precise[k]);
@@ -159,6 +165,7 @@ template <int KIND, int PREC>
 __device__ __forceinline__ float act(float x)
 {
     if constexpr (PREC == FAST) return act_fast<KIND>(x);
+    else if constexpr (KIND == GELU_ERF) return (float)act_precise<KIND>(x);
     else return nan_through(x, (float)act_precise<KIND>(x));
 }
 
@@ -172,8 +179,9 @@ __device__ __forceinline__ void act_times(float gate, float up, float& a, float&
         h = a * up;
     } else {
         double ad = act_precise<KIND>(gate);
-        a = nan_through(gate, (float)ad);
-        h = nan_through(gate, (float)(ad * (double)up));
+        a = (float)ad;
+        h = (float)(ad * (double)up);
+        if constexpr (KIND != GELU_ERF) { a = nan_through(gate, a); h = nan_through(gate, h); }
     }
 }
 
@@ -190,7 +198,8 @@ __device__ __forceinline__ float act_minus_min_signed(float x)
         v = (d < 0.0f) ? 0.0f : d;                      // keeps a NaN
     } else {
         double d = act_precise<KIND>(x) - (double)C;
-        v = nan_through(x, (float)((d < 0.0) ? 0.0 : d));
+        v = (float)((d < 0.0) ? 0.0 : d);               // keeps a NaN
+        if constexpr (KIND != GELU_ERF) v = nan_through(x, v);
     }
     return (x < KindConst<KIND>::T) ? -v : v;
 }
