@@ -1,6 +1,6 @@
 """Shared helpers of the GPU parity tests: tolerance rules and tensor plumbing.
 
-Tolerances (the reasons are derived in DESIGN.md, "Tolerances"):
+Tolerances:
   forward  : |gpu - f(x)| <= 2 ulp_D(f(x)), D the storage dtype; where
              |f(x)| < 2^-126 an absolute 2^-126 (gradual underflow and flush
              to zero both pass).

@@ -6,7 +6,7 @@ floating-point outputs are compared on a sample the oracle evaluates one by
 one (both ends of the tensor plus 2^20 random positions); the backward runs on
 what the ORACLE's forward saved.  The approximation error of q against the
 exact derivative (which the paper only plots) is written to
-gpurun_out/accuracy_report.json.
+accuracy_report.json in the folder GPU runs leave their files in.
 """
 import json
 import os
