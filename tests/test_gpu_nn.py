@@ -146,3 +146,26 @@ def test_sign_bit_act_linear_matches_torch_and_saves_one_tensor(kind, wiring):
     weight_bytes = layer.weight.numel() * 2
     assert ours - weight_bytes == x.numel() * 2
     assert base - weight_bytes == 2 * x.numel() * 2
+
+
+def test_whole_model_memory_saving_matches_the_papers_table(wiring):
+    """ViT-base built from its architecture parameters (random weights): swapping the 12 GELU modules for InvAct
+    layers cuts the stored activations by the 23.8 % the paper's memory table prints, to within a point."""
+    if wiring != "c++":
+        pytest.skip("one wiring is enough for a count of saved bytes")
+    pytest.importorskip("transformers")
+    from paper_2407_15545_amd import memory_table as M
+    make, inputs = M.build("vit", "sdpa")
+    torch.manual_seed(0)
+    model = make().to(device="cuda", dtype=torch.float32).train()
+    batch = inputs("cuda", torch.float32)
+    PT.say("memory table: ViT-base fp32")
+    base = M.saved_bytes(model, batch)
+    assert M.swap_activations(model) == 12
+    ours = M.saved_bytes(model, batch)
+    saving = 100 * (ours / base - 1)
+    assert -24.8 <= saving <= -22.8, saving
+    # the swapped model still runs backward
+    out = model(**batch).last_hidden_state
+    out.float().square().mean().backward()
+    assert all(p.grad is None or torch.isfinite(p.grad).all() for p in model.parameters())
