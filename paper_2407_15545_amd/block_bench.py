@@ -14,10 +14,14 @@ precision-bit InvAct layer in its place (the variants take turns, group by group
   geglu        act(Linear(2^10 -> 4*2^10)) * Linear(2^10 -> 4*2^10), batch 2^15; for InvAct
                also with the fused gated kernel (one launch for activation and product)
 
+  bert         BERT-base with its masked-LM head, batch 64 x 1024 tokens (Table 1, row 5)
+  llama        Llama-3.1-8B-shaped causal LM, batch 1 x 512 tokens (row 6)
+
 The GEMMs are torch's (hipBLASLt / rocBLAS); only the activation differs between
 the columns.  Inputs and weights are seeded random numbers: the table is about
-time, and the time of these kernels does not depend on the values.  The
-BERT and Llama rows of the table need the models and are not reproduced.
+time, and the time of these kernels does not depend on the values.  The two
+whole models are built from their architecture parameters (nothing is
+downloaded); a step is forward + loss + backward, without an optimizer.
 """
 import argparse
 import statistics
@@ -124,12 +128,61 @@ def time_block(module, x, iters, groups=5, graph=False):
     return time_steps({"m": prepare(module, x, graph)}, iters, groups)["m"]
 
 
+def model_rows(which, iters):
+    """Training-step time of whole models with torch's activation, InvAct and precision-bit InvAct."""
+    import transformers as T
+    from . import memory_table
+    if which == "bert":
+        name, td = "BERT-base (64 x 1024)", torch.float32
+        cfg = T.BertConfig(max_position_embeddings=1024)
+        make = lambda: T.BertForMaskedLM(cfg)
+        ids = torch.randint(0, cfg.vocab_size, (64, 1024), device="cuda")
+    else:
+        name, td = "Llama-3.1-8B (1 x 512)", torch.bfloat16
+        cfg = T.LlamaConfig(vocab_size=128256, hidden_size=4096, intermediate_size=14336, num_hidden_layers=32,
+                            num_attention_heads=32, num_key_value_heads=8, max_position_embeddings=8192,
+                            rope_theta=500000.0)
+        make = lambda: T.LlamaForCausalLM(cfg)
+        ids = torch.randint(0, cfg.vocab_size, (1, 512), device="cuda")
+    cfg._attn_implementation = "sdpa"
+    models = {}
+    previous = torch.get_default_dtype()
+    torch.set_default_dtype(td)
+    try:
+        for col in ("torch", "invact", "pbit") + (("fused",) if which == "llama" else ()):
+            torch.manual_seed(0)
+            with torch.device("cuda"):
+                models[col] = make().train()
+            if col == "fused":          # the gated MLP through the fused SwiGLU kernel: down(silu(gate(x)) * up(x))
+                glu = invact_nn.InvActGLU("silu")
+                for layer in models[col].model.layers:
+                    mlp = layer.mlp
+                    mlp.forward = (lambda x, m=mlp: m.down_proj(glu(m.gate_proj(x), m.up_proj(x))))
+            elif col != "torch":
+                memory_table.swap_activations(models[col], precision_bit=(col == "pbit"))
+    finally:
+        torch.set_default_dtype(previous)
+
+    def stepper(model):
+        def step():
+            model(input_ids=ids, labels=ids).loss.backward()
+            for p in model.parameters():
+                p.grad = None
+        for _ in range(2):
+            step()
+        torch.cuda.synchronize()
+        return step
+
+    res = time_steps({col: stepper(m) for col, m in models.items()}, iters, groups=3)
+    return name, {"bert": "fp32", "llama": "bf16"}[which], res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--dtypes", nargs="+", default=["bf16", "fp32"])
     ap.add_argument("--iters", type=int, default=20)
     ap.add_argument("--approximate", default="none", choices=["none", "tanh"])
-    ap.add_argument("--blocks", nargs="+", default=["plain", "linear", "mlp", "geglu"])
+    ap.add_argument("--blocks", nargs="+", default=["plain", "linear", "mlp", "geglu", "bert", "llama"])
     args = ap.parse_args()
     torch.cuda.set_device(0)
     torch.backends.cuda.matmul.allow_tf32 = False
@@ -171,6 +224,14 @@ def main():
             cell = lambda k: f"{res[k]:8.3f} ({100 * (res[k] / base - 1):+6.2f}%)" if k in res else ""
             print(f"{name:26s} {dt:5s} {base:9.3f} {cell('invact'):>18s} {cell('pbit'):>18s} {cell('fused'):>18s}", flush=True)
             del x
+            torch.cuda.empty_cache()
+    for which in ("bert", "llama"):
+        if which in args.blocks:
+            name, dt, res = model_rows(which, max(2, args.iters // 5))
+            base = res["torch"]
+            cell = lambda k: f"{res[k]:8.3f} ({100 * (res[k] / base - 1):+6.2f}%)"
+            print(f"{name:26s} {dt:5s} {base:9.3f} {cell('invact'):>18s} {cell('pbit'):>18s} "
+                  f"{cell('fused') if 'fused' in res else '':>18s}", flush=True)
             torch.cuda.empty_cache()
 
 

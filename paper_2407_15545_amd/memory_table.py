@@ -116,20 +116,23 @@ def fuse_quick_gelu(model):
     return n
 
 
-def swap_activations(model):
+def swap_activations(model, precision_bit=False):
     """Replace the models' activation modules by InvAct layers.  Returns how many were replaced."""
     from transformers import activations as A
     tanh_forms = tuple(c for c in (getattr(A, k, None) for k in ("NewGELUActivation", "GELUTanh", "PytorchGELUTanh")) if c)
+    silu_forms = tuple(c for c in (getattr(A, "SiLUActivation", None), torch.nn.SiLU) if c)
     n = 0
     for module in model.modules():
         for attr in ("intermediate_act_fn", "activation_fn", "act_fn"):
             fn = getattr(module, attr, None)
             if isinstance(fn, A.GELUActivation):
-                setattr(module, attr, invact_nn.InvActGELU())
+                setattr(module, attr, invact_nn.InvActGELU(precision_bit=precision_bit))
             elif isinstance(fn, (A.QuickGELUActivation, FusedQuickGELU)):
                 setattr(module, attr, InvActQuickGELU())
+            elif isinstance(fn, silu_forms):
+                setattr(module, attr, invact_nn.InvActSiLU(precision_bit=precision_bit))
             elif isinstance(fn, tanh_forms):
-                setattr(module, attr, invact_nn.InvActGELU(approximate="tanh"))
+                setattr(module, attr, invact_nn.InvActGELU(approximate="tanh", precision_bit=precision_bit))
             else:
                 continue
             n += 1
