@@ -64,6 +64,15 @@ def cpu_baseline(w, n_slice):
                                 "sample": f"first {n1} elements, {dt1:.2f} s"}
     except OSError:
         pass
+    # the exact branch-wise inverse (bisection), which only the accuracy reports use, timed on its own
+    n2 = min(n_slice, 1 << 20)
+    y_st = np.ascontiguousarray(as_[:n2])
+    s_bits = O.unpack(m, n_slice)[:n2]
+    t0 = time.perf_counter()
+    O.finv("silu", y_st, s_bits)
+    dt2 = time.perf_counter() - t0
+    out["inverse_by_bisection"] = {"value": round(n2 / dt2 / 1e6, 3), "unit": "M elements/s",
+                                   "sample": f"first {n2} saved activations, {dt2:.2f} s"}
     return out
 
 
