@@ -13,8 +13,9 @@
  *     as soon as the kernel is launched.
  *   - Tensors are flat and contiguous, `n` elements each; shape is the caller's
  *     business.  dtype selects the storage format of every floating-point
- *     tensor of the call (arithmetic is binary32 in registers, one
- *     round-to-nearest-even at the store).
+ *     tensor of the call (arithmetic is binary32 in registers -- binary64
+ *     in the forward of binary32 storage -- with one round-to-nearest-even
+ *     at the store).
  *   - `mask` holds invact_mask_bytes(n) bytes: element i is bit (i mod 8) of
  *     byte (i div 8), i.e. bit (i mod 64) of little-endian 64-bit word
  *     (i div 64) (Method, "Space-efficient Boolean Indicator").  The forward
