@@ -13,6 +13,7 @@ weights (nothing is downloaded) and fed random inputs of the shapes the appendix
   vit    ViT-base, patch 16, 224 x 224 image (12 x 768, MLP 3072, GELU)
   clip   CLIP ViT-L/14: text tower 12 x 768 / 77 tokens, vision tower 24 x 1024 / 224 x 224 image; its
          activation x * sigmoid(1.702 x) is SiLU with a rescaled argument and goes through the SiLU kernels
+  llama  (not in the paper's table, not run by default) Llama-3.1-8B shape, 512 tokens, bf16: a gated MLP
 
 Every tensor autograd saves during the forward (training mode) is counted once by its storage; parameters
 are left out, as in the paper.  The activation modules of the models are then swapped for the InvAct
@@ -96,6 +97,15 @@ def build(name, attn):
         make = lambda: T.CLIPModel(cfg)
         inputs = lambda dev, dt: {"input_ids": torch.randint(0, 49407, (1, 77), device=dev),
                                   "pixel_values": torch.randn(1, 3, 224, 224, device=dev, dtype=dt)}
+    elif name == "llama":               # not in the paper's table: a gated (SwiGLU) model, 512 tokens
+        cfg = T.LlamaConfig(vocab_size=128256, hidden_size=4096, intermediate_size=14336, num_hidden_layers=32,
+                            num_attention_heads=32, num_key_value_heads=8, max_position_embeddings=8192,
+                            rope_theta=500000.0)
+
+        def make():
+            with torch.device("cuda"):
+                return T.LlamaModel(cfg)
+        inputs = lambda dev, dt: {"input_ids": torch.randint(0, cfg.vocab_size, (1, 512), device=dev)}
     else:
         raise ValueError(name)
     for c in (cfg, getattr(cfg, "text_config", None), getattr(cfg, "vision_config", None)):
@@ -170,13 +180,28 @@ def main():
             for attn in args.attn:
                 make, inputs = build(name, attn)
                 torch.manual_seed(0)
-                model = make().to(device="cuda", dtype=td).train()
+                if name == "llama":     # 8 B parameters: created on the GPU, directly in the storage dtype
+                    if dt == "fp32":
+                        continue
+                    torch.set_default_dtype(td)
+                try:
+                    model = make().to(device="cuda", dtype=td).train()
+                finally:
+                    torch.set_default_dtype(torch.float32)
                 batch = inputs("cuda", td)
                 base = saved_bytes(model, batch)
                 fused = saved_bytes(model, batch) if fuse_quick_gelu(model) else None
                 replaced = swap_activations(model)
                 ours = saved_bytes(model, batch)
                 print(f"{name:6s} {dt:5s} {attn:9s} {base / 1e6:10.1f} {ours / 1e6:10.1f} {100 * (ours / base - 1):+7.1f}%  {replaced}", flush=True)
+                if name == "llama":     # the gated MLP as one fused layer: down(glu(gate(x), up(x)))
+                    glu = invact_nn.InvActGLU("silu")
+                    for layer in model.layers:
+                        mlp = layer.mlp
+                        mlp.forward = (lambda x, m=mlp: m.down_proj(glu(m.gate_proj(x), m.up_proj(x))))
+                    both = saved_bytes(model, batch)
+                    print(f"{'':6s} {'':5s} {'':9s} {base / 1e6:10.1f} {both / 1e6:10.1f} {100 * (both / base - 1):+7.1f}%  "
+                          f"with the fused SwiGLU layer", flush=True)
                 if fused is not None:
                     print(f"{'':6s} {'':5s} {'':9s} {fused / 1e6:10.1f} {ours / 1e6:10.1f} {100 * (ours / fused - 1):+7.1f}%  "
                           f"against the activation as one layer that saves its input", flush=True)
