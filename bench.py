@@ -104,6 +104,9 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
     torch.cuda.set_device(0)
+    from paper_2407_15545_amd import build as hip_build
+    if not os.path.exists(hip_build.LIB):               # nothing built yet: build, never fall back
+        hip_build.build(force=True)
     B.lib()                                              # fails loudly if the HIP library is missing
     if args.blocks_per_cu:
         B.set_blocks_per_cu(args.blocks_per_cu)
