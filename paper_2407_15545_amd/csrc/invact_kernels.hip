@@ -3,23 +3,27 @@
 //
 // Kernel shape.  All kernels are pure streaming maps, bound by HBM
 // bandwidth, so they share one skeleton.  The unit of work of a wavefront is a
-// "wave tile" of 512 consecutive elements = 64 mask bytes = eight 64-bit mask
-// words; each lane owns 8 of those elements (its "chunk"):
-//   bfloat16  lane L owns elements 8L .. 8L+7: one 128-bit access, and exactly
-//             mask byte L of the tile;
-//   binary32  lane L owns elements 4L .. 4L+3 and 256+4L .. 256+4L+3: two
-//             128-bit accesses, each fully coalesced across the wavefront (1 KiB
-//             contiguous; letting a lane own 32 contiguous bytes instead costs
-//             10-19 % of the bandwidth).  A lane then holds two nibbles of two
-//             different mask bytes; neighbouring lanes swap nibbles with one
-//             DPP move so that every lane again stores (or loads) one byte.
-// The canonical little-endian bit stream thus comes out of lane-local shifts.
+// "wave tile" of 64 chunks, a chunk being the elements one lane owns:
+//   bfloat16  8 elements per lane (tile of 512): lane L owns elements 8L .. 8L+7,
+//             one 128-bit access, and exactly mask byte L of the tile;
+//   binary32  4 elements per lane (tile of 256): one 128-bit access per tensor;
+//             a lane holds one nibble of mask byte L/2, neighbouring lanes
+//             exchange nibbles with one DPP move and the even one stores the
+//             byte (reading, both load it).  The forward kernels, whose
+//             binary64 arithmetic per element is long, take 8 elements per lane
+//             instead (tile of 512, elements 4L.. and 256+4L..: two coalesced
+//             accesses; letting a lane own 32 contiguous bytes would cost
+//             10-19 % of the bandwidth): eight independent chains hide the
+//             latency better (4-5 %), while every other kernel is 2-8 % faster
+//             with the smaller footprint per wavefront.
+// The canonical little-endian bit stream thus comes out of lane-local shifts,
+// whatever the tiling of the kernel that wrote it.
 // A lane keeps Op::kShape.unroll chunks in flight: all loads of a step are issued
 // before the first store, which is also what makes element-wise in-place use
 // (y == x and the like) safe.  The tensor accesses are non-temporal (each byte
-// is touched once); mask bytes go through the cache, because the 64 bytes a
-// wavefront touches are half a cache line.  The up to 511 elements past the
-// last full wave tile are handled one element per lane by the first wavefront,
+// is touched once); mask bytes go through the cache, because the 32 or 64 bytes
+// a wavefront touches are a fraction of a cache line.  The elements past the
+// last full wave tile (fewer than 512) are handled one element per lane by the first wavefront,
 // the mask word being formed by a wave64 ballot there (and zero padding coming
 // for free).
 //
@@ -61,7 +65,6 @@ using namespace invact_dev;
 #endif
 
 constexpr int  kThreads = INVACT_THREADS;
-constexpr int  kWaveTile = 512;                   // elements per wavefront and step
 constexpr bool kNonTemporal = INVACT_NT != 0;     // every byte is touched once: keep it out of the caches
 constexpr int  kDefaultBlocksPerCu = INVACT_DEFAULT_BLOCKS_PER_CU;   // 0: one tile per workgroup
 constexpr int  kWaveSlotsPerCu = 32;              // resident wavefronts a compute unit can hold
@@ -116,11 +119,76 @@ typedef float    f32x2 __attribute__((ext_vector_type(2)));
 // index: wave tile c / 64, lane c % 64.
 // ---------------------------------------------------------------------------
 
-template <int DT> struct Storage;
+template <int DT, int ELEMS> struct Storage;        // ELEMS = elements per lane and chunk
 
-template <> struct Storage<INVACT_FP32> {
+// Elements per lane for the streaming-bound operations: one 128-bit access per tensor.
+template <int DT> constexpr int lean_elems() { return DT == INVACT_FP32 ? 4 : 8; }
+
+// binary32, 4 elements per lane: one 128-bit access per tensor and a 256-element wave tile.
+template <> struct Storage<INVACT_FP32, 4> {
+    struct Raw { f32x4 a; };
+    static constexpr int kPrec = PRECISE;
+    static constexpr int kElems = 4;                    // elements per lane and chunk
+    static constexpr int kWaveTile = 64 * kElems;       // elements per wavefront and tile
+    static __device__ __forceinline__ Raw load(const void* p, size_t c)
+    {
+        return Raw{ld(reinterpret_cast<const f32x4*>(p) + c)};
+    }
+    static __device__ __forceinline__ void unpack(const Raw& r, float (&v)[4])
+    {
+        for (int j = 0; j < 4; ++j) v[j] = r.a[j];
+    }
+    static __device__ __forceinline__ void store(void* p, size_t c, const float (&v)[4])
+    {
+        st(reinterpret_cast<f32x4*>(p) + c, f32x4{v[0], v[1], v[2], v[3]});
+    }
+    // A lane owns the low (even lane) or high (odd lane) nibble of mask byte c / 2.  Writing: the two
+    // lanes exchange nibbles with one DPP move and the even one stores the byte.  Reading: both load it.
+    static __device__ __forceinline__ void store_mask(uint8_t* mask, size_t c, uint32_t m)
+    {
+        const uint32_t other = swap_with_neighbour(m);
+        if (!(c & 1)) st_mask(mask + (c >> 1), (uint8_t)(m | (other << 4)));
+    }
+    static __device__ __forceinline__ uint32_t load_mask(const uint8_t* mask, size_t c)
+    {
+        const uint32_t byte = ld_mask(mask + (c >> 1));
+        return (c & 1) ? (byte >> 4) : (byte & 0xFu);
+    }
+    static __device__ __forceinline__ float load1(const void* p, size_t i) { return reinterpret_cast<const float*>(p)[i]; }
+    static __device__ __forceinline__ void store1(void* p, size_t i, float v) { reinterpret_cast<float*>(p)[i] = v; }
+    // precision-bit variant: bit 0 of each stored pattern := bit j of m / read it back
+    static __device__ __forceinline__ float tag(float v, uint32_t bit)
+    {
+        return __uint_as_float((__float_as_uint(v) & ~1u) | bit);
+    }
+    static __device__ __forceinline__ uint32_t lsb(float v) { return __float_as_uint(v) & 1u; }
+    static __device__ __forceinline__ void store_tagged(void* p, size_t c, float (&v)[4], uint32_t m)
+    {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = tag(v[j], (m >> j) & 1u);
+        store(p, c, v);
+    }
+    static __device__ __forceinline__ uint32_t unpack_tagged(const Raw& r, float (&v)[4])
+    {
+        unpack(r, v);
+        uint32_t m = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) m |= lsb(v[j]) << j;
+        return m;
+    }
+    static __device__ __forceinline__ void store1_tagged(void* p, size_t i, float v, bool bit) { store1(p, i, tag(v, bit)); }
+    static __device__ __forceinline__ bool lsb1(const void* p, size_t i) { return lsb(load1(p, i)); }
+};
+
+// binary32, 8 elements per lane: elements 4L .. 4L+3 and 256+4L .. 256+4L+3 of a 512-element wave tile, i.e. two
+// coalesced 128-bit accesses (a lane owning 32 contiguous bytes costs 10-19 % of the bandwidth).  A lane then holds
+// two nibbles of two different mask bytes; neighbouring lanes swap nibbles with one DPP move so that every lane
+// stores (or loads) one byte.  Used where the arithmetic per element is long and more independent chains help.
+template <> struct Storage<INVACT_FP32, 8> {
     struct Raw { f32x4 a, b; };
     static constexpr int kPrec = PRECISE;
+    static constexpr int kElems = 8;
+    static constexpr int kWaveTile = 64 * kElems;
     // v[0..3] = elements 4L.., v[4..7] = elements 256 + 4L.. of the wave tile
     static __device__ __forceinline__ size_t vec_index(size_t c) { return (c >> 6) * 128 + (c & 63); }
     static __device__ __forceinline__ Raw load(const void* p, size_t c)
@@ -184,9 +252,12 @@ template <> struct Storage<INVACT_FP32> {
     static __device__ __forceinline__ bool lsb1(const void* p, size_t i) { return lsb(load1(p, i)); }
 };
 
-template <> struct Storage<INVACT_BF16> {
+// bfloat16, 8 elements per lane: one 128-bit access per tensor, and exactly mask byte L of the 512-element wave tile.
+template <> struct Storage<INVACT_BF16, 8> {
     struct Raw { u32x4 w; };
     static constexpr int kPrec = FAST;
+    static constexpr int kElems = 8;                    // elements per lane and chunk
+    static constexpr int kWaveTile = 64 * kElems;       // elements per wavefront and tile
     static __device__ __forceinline__ Raw load(const void* p, size_t c)
     {
         return Raw{ld(reinterpret_cast<const u32x4*>(p) + c)};
@@ -256,16 +327,16 @@ enum MaskMode { MASK_NONE = 0, MASK_WRITE = 1, MASK_READ = 2 };
 
 template <int KIND, int DT>
 struct FwdOp {                       // y = f(x), s = [x < T]
-    using S = Storage<DT>;
+    using S = Storage<DT, 8>;
     const void* x; void* y; uint8_t* mask;
     struct In { typename S::Raw x; };
     __device__ __forceinline__ void load(In& in, size_t c) const { in.x = S::load(x, c); }
     __device__ __forceinline__ void run(const In& in, size_t c) const
     {
-        float v[8]; S::unpack(in.x, v);
+        float v[S::kElems]; S::unpack(in.x, v);
         uint32_t m = 0;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
+        for (int j = 0; j < S::kElems; ++j) {
             m |= (uint32_t)(v[j] < KindConst<KIND>::T) << j;
             v[j] = act<KIND, S::kPrec>(v[j]);
         }
@@ -284,7 +355,7 @@ struct FwdOp {                       // y = f(x), s = [x < T]
 
 template <int KIND, int DT>
 struct BwdOp {                       // grad_x = grad_y * q(y, s)
-    using S = Storage<DT>;
+    using S = Storage<DT, lean_elems<DT>()>;
     const void* y; const uint8_t* mask; const void* gy; void* gx;
     struct In { typename S::Raw y, g; uint32_t m; };
     __device__ __forceinline__ void load(In& in, size_t c) const
@@ -293,9 +364,9 @@ struct BwdOp {                       // grad_x = grad_y * q(y, s)
     }
     __device__ __forceinline__ void run(const In& in, size_t c) const
     {
-        float a[8], g[8]; S::unpack(in.y, a); S::unpack(in.g, g);
+        float a[S::kElems], g[S::kElems]; S::unpack(in.y, a); S::unpack(in.g, g);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) g[j] = times_q<KIND, S::kPrec>(g[j], a[j], (in.m >> j) & 1u);
+        for (int j = 0; j < S::kElems; ++j) g[j] = times_q<KIND, S::kPrec>(g[j], a[j], (in.m >> j) & 1u);
         S::store(gx, c, g);
     }
     __device__ __forceinline__ bool scalar(size_t i, bool bit) const
@@ -304,12 +375,12 @@ struct BwdOp {                       // grad_x = grad_y * q(y, s)
         return bit;
     }
     static constexpr int kMask = MASK_READ;
-    static constexpr Shape kShape = pick<DT>({2, 10}, {1, 32});   // {tiles, resident cap}: binary32, bfloat16
+    static constexpr Shape kShape = pick<DT>({1, 24}, {1, 32});   // {tiles, resident cap}: binary32, bfloat16
 };
 
 template <int KIND, int DT>
 struct GluFwdOp {                    // act = f(gate), s = [gate < T], h = f(gate) * up
-    using S = Storage<DT>;
+    using S = Storage<DT, lean_elems<DT>()>;
     const void* gate; const void* up; void* act_out; void* h; uint8_t* mask;
     struct In { typename S::Raw g, u; };
     __device__ __forceinline__ void load(In& in, size_t c) const
@@ -318,10 +389,10 @@ struct GluFwdOp {                    // act = f(gate), s = [gate < T], h = f(gat
     }
     __device__ __forceinline__ void run(const In& in, size_t c) const
     {
-        float v[8], u[8]; S::unpack(in.g, v); S::unpack(in.u, u);
+        float v[S::kElems], u[S::kElems]; S::unpack(in.g, v); S::unpack(in.u, u);
         uint32_t m = 0;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
+        for (int j = 0; j < S::kElems; ++j) {
             m |= (uint32_t)(v[j] < KindConst<KIND>::T) << j;
             act_times<KIND, S::kPrec>(v[j], u[j], v[j], u[j]);
         }
@@ -338,12 +409,12 @@ struct GluFwdOp {                    // act = f(gate), s = [gate < T], h = f(gat
         return v < KindConst<KIND>::T;
     }
     static constexpr int kMask = MASK_WRITE;
-    static constexpr Shape kShape = pick<DT>({2, 7}, {1, 16});   // {tiles, resident cap}: binary32, bfloat16
+    static constexpr Shape kShape = pick<DT>({1, 16}, {1, 16});   // {tiles, resident cap}: binary32, bfloat16
 };
 
 template <int KIND, int DT>
 struct GluBwdOp {                    // grad_up = grad_h * act ; grad_gate = grad_h * up * q(act, s)
-    using S = Storage<DT>;
+    using S = Storage<DT, lean_elems<DT>()>;
     const void* act_in; const void* up; const uint8_t* mask; const void* gh; void* ggate; void* gup;
     struct In { typename S::Raw a, u, g; uint32_t m; };
     __device__ __forceinline__ void load(In& in, size_t c) const
@@ -352,9 +423,9 @@ struct GluBwdOp {                    // grad_up = grad_h * act ; grad_gate = gra
     }
     __device__ __forceinline__ void run(const In& in, size_t c) const
     {
-        float a[8], u[8], g[8]; S::unpack(in.a, a); S::unpack(in.u, u); S::unpack(in.g, g);
+        float a[S::kElems], u[S::kElems], g[S::kElems]; S::unpack(in.a, a); S::unpack(in.u, u); S::unpack(in.g, g);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
+        for (int j = 0; j < S::kElems; ++j) {
             float gate_grad = times_q<KIND, S::kPrec>(g[j], u[j], a[j], (in.m >> j) & 1u);
             a[j] = g[j] * a[j];                  // grad_up
             u[j] = gate_grad;                    // grad_gate
@@ -370,22 +441,22 @@ struct GluBwdOp {                    // grad_up = grad_h * act ; grad_gate = gra
         return bit;
     }
     static constexpr int kMask = MASK_READ;
-    static constexpr Shape kShape = pick<DT>({2, 7}, {1, 16});   // {tiles, resident cap}: binary32, bfloat16
+    static constexpr Shape kShape = pick<DT>({1, 16}, {1, 16});   // {tiles, resident cap}: binary32, bfloat16
 };
 
 // Precision-bit variant: no mask tensor, the indicator travels in bit 0 of y.
 template <int KIND, int DT>
 struct PbitFwdOp {                   // y = f(x) with bit 0 := [x < T]
-    using S = Storage<DT>;
+    using S = Storage<DT, 8>;
     const void* x; void* y;
     struct In { typename S::Raw x; };
     __device__ __forceinline__ void load(In& in, size_t c) const { in.x = S::load(x, c); }
     __device__ __forceinline__ void run(const In& in, size_t c) const
     {
-        float v[8]; S::unpack(in.x, v);
+        float v[S::kElems]; S::unpack(in.x, v);
         uint32_t m = 0;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
+        for (int j = 0; j < S::kElems; ++j) {
             m |= (uint32_t)(v[j] < KindConst<KIND>::T) << j;
             v[j] = act<KIND, S::kPrec>(v[j]);
         }
@@ -403,17 +474,17 @@ struct PbitFwdOp {                   // y = f(x) with bit 0 := [x < T]
 
 template <int KIND, int DT>
 struct PbitBwdOp {                   // s = bit 0 of y; grad_x = grad_y * q(y, s)
-    using S = Storage<DT>;
+    using S = Storage<DT, lean_elems<DT>()>;
     const void* y; const void* gy; void* gx;
     struct In { typename S::Raw y, g; };
     __device__ __forceinline__ void load(In& in, size_t c) const { in.y = S::load(y, c); in.g = S::load(gy, c); }
     __device__ __forceinline__ void run(const In& in, size_t c) const
     {
-        float a[8], g[8];
+        float a[S::kElems], g[S::kElems];
         const uint32_t m = S::unpack_tagged(in.y, a);
         S::unpack(in.g, g);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) g[j] = times_q<KIND, S::kPrec>(g[j], a[j], (m >> j) & 1u);
+        for (int j = 0; j < S::kElems; ++j) g[j] = times_q<KIND, S::kPrec>(g[j], a[j], (m >> j) & 1u);
         S::store(gx, c, g);
     }
     __device__ __forceinline__ bool scalar(size_t i, bool) const
@@ -422,22 +493,22 @@ struct PbitBwdOp {                   // s = bit 0 of y; grad_x = grad_y * q(y, s
         return false;
     }
     static constexpr int kMask = MASK_NONE;
-    static constexpr Shape kShape = pick<DT>({2, 8}, {1, 32});   // {tiles, resident cap}: binary32, bfloat16
+    static constexpr Shape kShape = pick<DT>({1, 24}, {1, 32});   // {tiles, resident cap}: binary32, bfloat16
 };
 
 // Sign-bit variant: no mask tensor and an exact forward; the saved tensor is f(x) - min f, which is
 // never negative, with the indicator in its sign bit.  Whoever consumes it adds the minimum back.
 template <int KIND, int DT>
 struct SbitFwdOp {                   // y_tagged = +-(f(x) - C), sign bit := [x < T]
-    using S = Storage<DT>;
+    using S = Storage<DT, 8>;
     const void* x; void* yt;
     struct In { typename S::Raw x; };
     __device__ __forceinline__ void load(In& in, size_t c) const { in.x = S::load(x, c); }
     __device__ __forceinline__ void run(const In& in, size_t c) const
     {
-        float v[8]; S::unpack(in.x, v);
+        float v[S::kElems]; S::unpack(in.x, v);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) v[j] = act_minus_min_signed<KIND, S::kPrec>(v[j]);
+        for (int j = 0; j < S::kElems; ++j) v[j] = act_minus_min_signed<KIND, S::kPrec>(v[j]);
         S::store(yt, c, v);
     }
     __device__ __forceinline__ bool scalar(size_t i, bool) const
@@ -451,15 +522,15 @@ struct SbitFwdOp {                   // y_tagged = +-(f(x) - C), sign bit := [x 
 
 template <int KIND, int DT>
 struct SbitDecodeOp {                // y = |y_tagged| + C
-    using S = Storage<DT>;
+    using S = Storage<DT, lean_elems<DT>()>;
     const void* yt; void* y;
     struct In { typename S::Raw y; };
     __device__ __forceinline__ void load(In& in, size_t c) const { in.y = S::load(yt, c); }
     __device__ __forceinline__ void run(const In& in, size_t c) const
     {
-        float v[8]; S::unpack(in.y, v);
+        float v[S::kElems]; S::unpack(in.y, v);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) v[j] = fabsf(v[j]) + KindConst<KIND>::fT;
+        for (int j = 0; j < S::kElems; ++j) v[j] = fabsf(v[j]) + KindConst<KIND>::fT;
         S::store(y, c, v);
     }
     __device__ __forceinline__ bool scalar(size_t i, bool) const
@@ -468,12 +539,12 @@ struct SbitDecodeOp {                // y = |y_tagged| + C
         return false;
     }
     static constexpr int kMask = MASK_NONE;
-    static constexpr Shape kShape = pick<DT>({2, 32}, {1, 32});   // {tiles, resident cap}: binary32, bfloat16
+    static constexpr Shape kShape = pick<DT>({2, 20}, {1, 32});   // {tiles, resident cap}: binary32, bfloat16
 };
 
 template <int KIND, int DT>
 struct SbitBwdOp {                   // s = sign bit of y_tagged; grad_x = grad_y * q(|y_tagged| + C, s)
-    using S = Storage<DT>;
+    using S = Storage<DT, lean_elems<DT>()>;
     const void* yt; const void* gy; void* gx;
     struct In { typename S::Raw y, g; };
     __device__ __forceinline__ void load(In& in, size_t c) const { in.y = S::load(yt, c); in.g = S::load(gy, c); }
@@ -483,11 +554,11 @@ struct SbitBwdOp {                   // s = sign bit of y_tagged; grad_x = grad_
     }
     __device__ __forceinline__ void run(const In& in, size_t c) const
     {
-        float a[8], g[8];
+        float a[S::kElems], g[S::kElems];
         S::unpack(in.y, a);
         S::unpack(in.g, g);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) g[j] = one(g[j], a[j]);
+        for (int j = 0; j < S::kElems; ++j) g[j] = one(g[j], a[j]);
         S::store(gx, c, g);
     }
     __device__ __forceinline__ bool scalar(size_t i, bool) const
@@ -496,7 +567,7 @@ struct SbitBwdOp {                   // s = sign bit of y_tagged; grad_x = grad_
         return false;
     }
     static constexpr int kMask = MASK_NONE;
-    static constexpr Shape kShape = pick<DT>({2, 8}, {1, 32});   // {tiles, resident cap}: binary32, bfloat16
+    static constexpr Shape kShape = pick<DT>({1, 24}, {1, 32});   // {tiles, resident cap}: binary32, bfloat16
 };
 
 // ---------------------------------------------------------------------------
@@ -513,6 +584,7 @@ template <class Op, bool PERSISTENT>
 __global__ __launch_bounds__(kThreads) void stream_kernel(const Op op, const size_t n)
 {
     constexpr int kUnroll = Op::kShape.unroll;
+    constexpr size_t kWaveTile = Op::S::kWaveTile;
     const size_t wave_tiles = n / kWaveTile;
     const size_t chunks = wave_tiles * 64;
 
@@ -620,7 +692,7 @@ template <class Op>
 int launch(const Op& op, size_t n, hipStream_t stream)
 {
     constexpr int kUnroll = Op::kShape.unroll;
-    const size_t chunks = (n / kWaveTile) * 64;
+    const size_t chunks = (n / Op::S::kWaveTile) * 64;
     const int per_cu = g_blocks_per_cu.load(std::memory_order_relaxed);
     if (per_cu == 0) {
         size_t blocks = (chunks + kThreads * kUnroll - 1) / (kThreads * kUnroll);
