@@ -55,7 +55,7 @@ typedef enum {
     INVACT_ERR_NULL,        /* a required pointer is NULL (and n > 0)          */
     INVACT_ERR_ALIGN,       /* a pointer is not aligned as required            */
     INVACT_ERR_SIZE,        /* n is too large: for the mask size to fit size_t, or
-                               for one launch (2^31 workgroups of 512 or 1024 elements) */
+                               for one launch (2^31 workgroups of 256 to 1024 elements) */
     INVACT_ERR_HIP          /* the HIP runtime refused the launch              */
 } invact_status;
 
