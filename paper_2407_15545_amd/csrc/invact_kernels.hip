@@ -57,25 +57,24 @@ using namespace invact_dev;
 #ifndef INVACT_MASK_NT
 #define INVACT_MASK_NT 0
 #endif
-#ifndef INVACT_THREADS
-#define INVACT_THREADS 64
-#endif
 #ifndef INVACT_DEFAULT_BLOCKS_PER_CU
 #define INVACT_DEFAULT_BLOCKS_PER_CU 0
 #endif
 
-constexpr int  kThreads = INVACT_THREADS;
 constexpr bool kNonTemporal = INVACT_NT != 0;     // every byte is touched once: keep it out of the caches
 constexpr int  kDefaultBlocksPerCu = INVACT_DEFAULT_BLOCKS_PER_CU;   // 0: one tile per workgroup
 constexpr int  kWaveSlotsPerCu = 32;              // resident wavefronts a compute unit can hold
 
-// Launch shape of an operation: wave tiles per wavefront and the cap on resident
-// workgroups per compute unit (kWaveSlotsPerCu: no cap).
-struct Shape { int unroll, resident; };
+// Launch shape of an operation: wave tiles per wavefront, the cap on resident workgroups per compute
+// unit (none if they would fill the kWaveSlotsPerCu slots anyway) and the threads of a workgroup.
+struct Shape { int unroll, resident, threads = 64; };
 template <int DT> constexpr Shape pick(Shape binary32, Shape bfloat16)
 {
 #ifdef INVACT_UNROLL_ALL                           // build variants for sweeps
     binary32.unroll = bfloat16.unroll = INVACT_UNROLL_ALL;
+#endif
+#ifdef INVACT_THREADS
+    binary32.threads = bfloat16.threads = INVACT_THREADS;
 #endif
     return DT == INVACT_FP32 ? binary32 : bfloat16;
 }
@@ -581,8 +580,9 @@ struct SbitBwdOp {                   // s = sign bit of y_tagged; grad_x = grad_
 // inside the tensor or entirely outside: every branch below is wave-uniform
 // (the neighbour swap of the binary32 mask needs whole quads).
 template <class Op, bool PERSISTENT>
-__global__ __launch_bounds__(kThreads) void stream_kernel(const Op op, const size_t n)
+__global__ __launch_bounds__(Op::kShape.threads) void stream_kernel(const Op op, const size_t n)
 {
+    constexpr int kThreads = Op::kShape.threads;
     constexpr int kUnroll = Op::kShape.unroll;
     constexpr size_t kWaveTile = Op::S::kWaveTile;
     const size_t wave_tiles = n / kWaveTile;
@@ -673,7 +673,7 @@ bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) &
 template <class Op>
 unsigned occupancy_cap_lds(int resident)
 {
-    if (resident <= 0 || resident * (kThreads / 64) >= kWaveSlotsPerCu) return 0;   // the hardware's own limit
+    if (resident <= 0 || resident * (Op::kShape.threads / 64) >= kWaveSlotsPerCu) return 0;   // the hardware's own limit
     static std::atomic<uint64_t> prepared{0};
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
@@ -692,6 +692,7 @@ template <class Op>
 int launch(const Op& op, size_t n, hipStream_t stream)
 {
     constexpr int kUnroll = Op::kShape.unroll;
+    constexpr int kThreads = Op::kShape.threads;
     const size_t chunks = (n / Op::S::kWaveTile) * 64;
     const int per_cu = g_blocks_per_cu.load(std::memory_order_relaxed);
     if (per_cu == 0) {
