@@ -54,24 +54,6 @@ def build_torch_extension(verbose=False):
     return TORCH_EXT
 
 
-TOOLS = {"membench": "-O3", "unit_accuracy": "-O2", "unit_rates": "-O3"}
-
-
-def build_tools(verbose=False):
-    """Compile the stand-alone probes of the machine (streaming ceiling, unit accuracy, issue rates)."""
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    out = []
-    for name, opt in TOOLS.items():
-        cmd = [hipcc, "--offload-arch=gfx950", opt, "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-               "-Wno-unused-command-line-argument", "-o", os.path.join(HERE, name),
-               os.path.join(HERE, "csrc", name + ".hip")]
-        if verbose:
-            print(" ".join(cmd), flush=True)
-        subprocess.run(cmd, check=True)
-        out.append(os.path.join(HERE, name))
-    return out
-
-
 if __name__ == "__main__":
     # python -m paper_2407_15545_amd.build [-o variant.so] [-DINVACT_UNROLL_ALL=2 ...]
     argv = sys.argv[1:]
@@ -82,5 +64,4 @@ if __name__ == "__main__":
         print(out)
     else:
         print(build(force=True, verbose=True, extra=argv))
-        print(*build_tools(verbose=True), sep="\n")
         print(build_torch_extension(verbose=True))

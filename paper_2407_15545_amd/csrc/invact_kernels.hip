@@ -51,54 +51,73 @@ namespace {
 
 using namespace invact_dev;
 
-#ifndef INVACT_NT
-#define INVACT_NT 1
+#ifndef INVACT_LD_AUX
+#define INVACT_LD_AUX 2            // nt
 #endif
-#ifndef INVACT_MASK_NT
-#define INVACT_MASK_NT 0
+#ifndef INVACT_ST_AUX
+#define INVACT_ST_AUX 18           // nt sc1
+#endif
+#ifndef INVACT_MASK_AUX
+#define INVACT_MASK_AUX 0
 #endif
 #ifndef INVACT_DEFAULT_BLOCKS_PER_CU
 #define INVACT_DEFAULT_BLOCKS_PER_CU 0
 #endif
 
-constexpr bool kNonTemporal = INVACT_NT != 0;     // every byte is touched once: keep it out of the caches
+// Cache-policy bits of the buffer instructions (the `aux` operand): 1 = sc0, 2 = nt, 16 = sc1.
+// Every tensor byte is touched once, so loads carry the non-temporal hint (worth 4-8 % over plain
+// loads); stores carry nt and sc1, which on this machine is another 1.5-2 % over nt alone for a
+// mix of read and write streams under the occupancy cap the gated kernels use (measured with a
+// plain copy kernel of the same stream mix: 3 reads + 2 writes 6.65 -> 6.76 TB/s).
+constexpr int kLoadAux = INVACT_LD_AUX, kStoreAux = INVACT_ST_AUX, kMaskAux = INVACT_MASK_AUX;
 constexpr int  kDefaultBlocksPerCu = INVACT_DEFAULT_BLOCKS_PER_CU;   // 0: one tile per workgroup
 constexpr int  kWaveSlotsPerCu = 32;              // resident wavefronts a compute unit can hold
+constexpr int  kWave = 64;                        // a workgroup is one wavefront
 
-// Launch shape of an operation: wave tiles per wavefront, the cap on resident workgroups per compute
-// unit (none if they would fill the kWaveSlotsPerCu slots anyway) and the threads of a workgroup.
-struct Shape { int unroll, resident, threads = 64; };
+// Launch shape of an operation: wave tiles per wavefront and the cap on resident wavefronts per
+// compute unit (none if they would fill the kWaveSlotsPerCu slots anyway).
+struct Shape { int unroll, resident; };
 template <int DT> constexpr Shape pick(Shape binary32, Shape bfloat16)
 {
 #ifdef INVACT_UNROLL_ALL                           // build variants for sweeps
     binary32.unroll = bfloat16.unroll = INVACT_UNROLL_ALL;
 #endif
-#ifdef INVACT_THREADS
-    binary32.threads = bfloat16.threads = INVACT_THREADS;
-#endif
     return DT == INVACT_FP32 ? binary32 : bfloat16;
 }
 
-template <class T> __device__ __forceinline__ T ld(const T* p)
+typedef float    f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16   bf16x2 __attribute__((ext_vector_type(2)));
+typedef float    f32x2 __attribute__((ext_vector_type(2)));
+
+// A wave tile's piece of a tensor as a raw buffer: base = p + offset lives in scalar registers (the
+// tile index is the workgroup's), the lane supplies a 32-bit byte offset, and the extent makes the
+// hardware drop anything addressed outside the piece.  No 64-bit vector address arithmetic.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t tile_buffer(const void* p, size_t offset, unsigned bytes)
 {
-    if constexpr (kNonTemporal) return __builtin_nontemporal_load(p); else return *p;
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(static_cast<const char*>(p)) + offset, 0, (int)bytes,
+                                             0x00020000 /* untyped 32-bit data, no swizzle */);
 }
-template <class T> __device__ __forceinline__ void st(T* p, T v)
+__device__ __forceinline__ u32x4 ld128(__amdgpu_buffer_rsrc_t r, unsigned byte)
 {
-    if constexpr (kNonTemporal) __builtin_nontemporal_store(v, p); else *p = v;
+    return __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte, 0, kLoadAux);
+}
+__device__ __forceinline__ void st128(__amdgpu_buffer_rsrc_t r, unsigned byte, u32x4 v)
+{
+    __builtin_amdgcn_raw_buffer_store_b128(v, r, (int)byte, 0, kStoreAux);
 }
 // The mask moves 64 bytes per wavefront and step, half a cache line: it goes through the cache,
 // so that the two halves of a line reach HBM as one write.  On the read side the two wavefronts
 // that share a line sit on different XCDs (consecutive workgroups do), each with its own L2, so
 // the line is fetched twice: 1.2 % more read traffic for the gated backward, which is cheaper than
 // keeping the pair on one XCD (measured 0.5-6 % slower).
-__device__ __forceinline__ void st_mask(uint8_t* p, uint8_t v)
+__device__ __forceinline__ uint32_t ld8(__amdgpu_buffer_rsrc_t r, unsigned byte)
 {
-    if constexpr (kNonTemporal && INVACT_MASK_NT != 0) __builtin_nontemporal_store(v, p); else *p = v;
+    return __builtin_amdgcn_raw_buffer_load_b8(r, (int)byte, 0, kMaskAux);
 }
-__device__ __forceinline__ uint8_t ld_mask(const uint8_t* p)
+__device__ __forceinline__ void st8(__amdgpu_buffer_rsrc_t r, unsigned byte, uint32_t v)
 {
-    if constexpr (kNonTemporal && INVACT_MASK_NT != 0) return __builtin_nontemporal_load(p); else return *p;
+    __builtin_amdgcn_raw_buffer_store_b8((uint8_t)v, r, (int)byte, 0, kMaskAux);
 }
 
 // value of the neighbouring lane (lane ^ 1); every lane of the quad must be active
@@ -107,15 +126,10 @@ __device__ __forceinline__ uint32_t swap_with_neighbour(uint32_t v)
     return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1 /* quad_perm [1,0,3,2] */, 0xF, 0xF, true);
 }
 
-typedef float    f32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef __bf16   bf16x2 __attribute__((ext_vector_type(2)));
-typedef float    f32x2 __attribute__((ext_vector_type(2)));
-
 // ---------------------------------------------------------------------------
-// Storage formats: one chunk (8 elements of one lane) <-> 8 floats in
-// registers, and the chunk's 8 mask bits <-> memory.  `c` is the global chunk
-// index: wave tile c / 64, lane c % 64.
+// Storage formats: one chunk (the elements one lane owns in a wave tile) <->
+// floats in registers, and the chunk's mask bits <-> memory.  `t` is the wave
+// tile (wave-uniform: it comes from the workgroup index), `lane` the lane.
 // ---------------------------------------------------------------------------
 
 template <int DT, int ELEMS> struct Storage;        // ELEMS = elements per lane and chunk
@@ -123,49 +137,57 @@ template <int DT, int ELEMS> struct Storage;        // ELEMS = elements per lane
 // Elements per lane for the streaming-bound operations: one 128-bit access per tensor.
 template <int DT> constexpr int lean_elems() { return DT == INVACT_FP32 ? 4 : 8; }
 
-// binary32, 4 elements per lane: one 128-bit access per tensor and a 256-element wave tile.
-template <> struct Storage<INVACT_FP32, 4> {
-    struct Raw { f32x4 a; };
+// What the binary32 layouts share: scalar accesses for the tail and the precision-bit tag.
+struct Binary32 {
     static constexpr int kPrec = PRECISE;
-    static constexpr int kElems = 4;                    // elements per lane and chunk
-    static constexpr int kWaveTile = 64 * kElems;       // elements per wavefront and tile
-    static __device__ __forceinline__ Raw load(const void* p, size_t c)
-    {
-        return Raw{ld(reinterpret_cast<const f32x4*>(p) + c)};
-    }
-    static __device__ __forceinline__ void unpack(const Raw& r, float (&v)[4])
-    {
-        for (int j = 0; j < 4; ++j) v[j] = r.a[j];
-    }
-    static __device__ __forceinline__ void store(void* p, size_t c, const float (&v)[4])
-    {
-        st(reinterpret_cast<f32x4*>(p) + c, f32x4{v[0], v[1], v[2], v[3]});
-    }
-    // A lane owns the low (even lane) or high (odd lane) nibble of mask byte c / 2.  Writing: the two
-    // lanes exchange nibbles with one DPP move and the even one stores the byte.  Reading: both load it.
-    static __device__ __forceinline__ void store_mask(uint8_t* mask, size_t c, uint32_t m)
-    {
-        const uint32_t other = swap_with_neighbour(m);
-        if (!(c & 1)) st_mask(mask + (c >> 1), (uint8_t)(m | (other << 4)));
-    }
-    static __device__ __forceinline__ uint32_t load_mask(const uint8_t* mask, size_t c)
-    {
-        const uint32_t byte = ld_mask(mask + (c >> 1));
-        return (c & 1) ? (byte >> 4) : (byte & 0xFu);
-    }
     static __device__ __forceinline__ float load1(const void* p, size_t i) { return reinterpret_cast<const float*>(p)[i]; }
     static __device__ __forceinline__ void store1(void* p, size_t i, float v) { reinterpret_cast<float*>(p)[i] = v; }
-    // precision-bit variant: bit 0 of each stored pattern := bit j of m / read it back
+    // precision-bit variant: bit 0 of the stored pattern := the indicator / read it back
     static __device__ __forceinline__ float tag(float v, uint32_t bit)
     {
         return __uint_as_float((__float_as_uint(v) & ~1u) | bit);
     }
     static __device__ __forceinline__ uint32_t lsb(float v) { return __float_as_uint(v) & 1u; }
-    static __device__ __forceinline__ void store_tagged(void* p, size_t c, float (&v)[4], uint32_t m)
+    static __device__ __forceinline__ void store1_tagged(void* p, size_t i, float v, bool bit) { store1(p, i, tag(v, bit)); }
+    static __device__ __forceinline__ bool lsb1(const void* p, size_t i) { return lsb(load1(p, i)); }
+};
+
+// binary32, 4 elements per lane: one 128-bit access per tensor and a 256-element wave tile.
+template <> struct Storage<INVACT_FP32, 4> : Binary32 {
+    struct Raw { u32x4 a; };
+    static constexpr int kElems = 4;                    // elements per lane and chunk
+    static constexpr int kWaveTile = kWave * kElems;    // elements per wavefront and tile
+    static constexpr unsigned kTileBytes = kWaveTile * 4, kMaskBytes = kWaveTile / 8;
+    static __device__ __forceinline__ Raw load(const void* p, size_t t, unsigned lane)
+    {
+        return Raw{ld128(tile_buffer(p, t * kTileBytes, kTileBytes), lane * 16)};
+    }
+    static __device__ __forceinline__ void unpack(const Raw& r, float (&v)[4])
+    {
+        for (int j = 0; j < 4; ++j) v[j] = __uint_as_float(r.a[j]);
+    }
+    static __device__ __forceinline__ void store(void* p, size_t t, unsigned lane, const float (&v)[4])
+    {
+        st128(tile_buffer(p, t * kTileBytes, kTileBytes), lane * 16,
+              u32x4{__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])});
+    }
+    // A lane owns the low (even lane) or high (odd lane) nibble of mask byte lane / 2 of the tile.  Writing: the two
+    // lanes exchange nibbles with one DPP move and the even one stores the byte.  Reading: both load it.
+    static __device__ __forceinline__ void store_mask(uint8_t* mask, size_t t, unsigned lane, uint32_t m)
+    {
+        const uint32_t other = swap_with_neighbour(m);
+        if (!(lane & 1)) st8(tile_buffer(mask, t * kMaskBytes, kMaskBytes), lane >> 1, m | (other << 4));
+    }
+    static __device__ __forceinline__ uint32_t load_mask(const uint8_t* mask, size_t t, unsigned lane)
+    {
+        const uint32_t byte = ld8(tile_buffer(mask, t * kMaskBytes, kMaskBytes), lane >> 1);
+        return (lane & 1) ? (byte >> 4) : (byte & 0xFu);
+    }
+    static __device__ __forceinline__ void store_tagged(void* p, size_t t, unsigned lane, float (&v)[4], uint32_t m)
     {
 #pragma unroll
         for (int j = 0; j < 4; ++j) v[j] = tag(v[j], (m >> j) & 1u);
-        store(p, c, v);
+        store(p, t, lane, v);
     }
     static __device__ __forceinline__ uint32_t unpack_tagged(const Raw& r, float (&v)[4])
     {
@@ -175,69 +197,55 @@ template <> struct Storage<INVACT_FP32, 4> {
         for (int j = 0; j < 4; ++j) m |= lsb(v[j]) << j;
         return m;
     }
-    static __device__ __forceinline__ void store1_tagged(void* p, size_t i, float v, bool bit) { store1(p, i, tag(v, bit)); }
-    static __device__ __forceinline__ bool lsb1(const void* p, size_t i) { return lsb(load1(p, i)); }
 };
 
 // binary32, 8 elements per lane: elements 4L .. 4L+3 and 256+4L .. 256+4L+3 of a 512-element wave tile, i.e. two
 // coalesced 128-bit accesses (a lane owning 32 contiguous bytes costs 10-19 % of the bandwidth).  A lane then holds
 // two nibbles of two different mask bytes; neighbouring lanes swap nibbles with one DPP move so that every lane
 // stores (or loads) one byte.  Used where the arithmetic per element is long and more independent chains help.
-template <> struct Storage<INVACT_FP32, 8> {
-    struct Raw { f32x4 a, b; };
-    static constexpr int kPrec = PRECISE;
+template <> struct Storage<INVACT_FP32, 8> : Binary32 {
+    struct Raw { u32x4 a, b; };
     static constexpr int kElems = 8;
-    static constexpr int kWaveTile = 64 * kElems;
+    static constexpr int kWaveTile = kWave * kElems;
+    static constexpr unsigned kTileBytes = kWaveTile * 4, kMaskBytes = kWaveTile / 8;
     // v[0..3] = elements 4L.., v[4..7] = elements 256 + 4L.. of the wave tile
-    static __device__ __forceinline__ size_t vec_index(size_t c) { return (c >> 6) * 128 + (c & 63); }
-    static __device__ __forceinline__ Raw load(const void* p, size_t c)
+    static __device__ __forceinline__ Raw load(const void* p, size_t t, unsigned lane)
     {
-        const f32x4* q = reinterpret_cast<const f32x4*>(p) + vec_index(c);
-        return Raw{ld(q), ld(q + 64)};
+        const __amdgpu_buffer_rsrc_t r = tile_buffer(p, t * kTileBytes, kTileBytes);
+        return Raw{ld128(r, lane * 16), ld128(r, 1024 + lane * 16)};
     }
     static __device__ __forceinline__ void unpack(const Raw& r, float (&v)[8])
     {
-        for (int j = 0; j < 4; ++j) { v[j] = r.a[j]; v[4 + j] = r.b[j]; }
+        for (int j = 0; j < 4; ++j) { v[j] = __uint_as_float(r.a[j]); v[4 + j] = __uint_as_float(r.b[j]); }
     }
-    static __device__ __forceinline__ void store(void* p, size_t c, const float (&v)[8])
+    static __device__ __forceinline__ void store(void* p, size_t t, unsigned lane, const float (&v)[8])
     {
-        f32x4* q = reinterpret_cast<f32x4*>(p) + vec_index(c);
-        st(q, f32x4{v[0], v[1], v[2], v[3]});
-        st(q + 64, f32x4{v[4], v[5], v[6], v[7]});
+        const __amdgpu_buffer_rsrc_t r = tile_buffer(p, t * kTileBytes, kTileBytes);
+        st128(r, lane * 16, u32x4{__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])});
+        st128(r, 1024 + lane * 16, u32x4{__float_as_uint(v[4]), __float_as_uint(v[5]), __float_as_uint(v[6]), __float_as_uint(v[7])});
     }
     // Bits 0-3 of m belong to byte L/2 of the tile (low nibble for even L), bits
     // 4-7 to byte 32 + L/2.  Even lanes end up with the first byte of the pair,
     // odd lanes with the second.
-    static __device__ __forceinline__ size_t mask_index(size_t c)
-    {
-        return (c >> 6) * 64 + ((c & 1) ? 32 : 0) + ((c & 63) >> 1);
-    }
-    static __device__ __forceinline__ void store_mask(uint8_t* mask, size_t c, uint32_t m)
+    static __device__ __forceinline__ unsigned mask_byte(unsigned lane) { return ((lane & 1) ? 32 : 0) + (lane >> 1); }
+    static __device__ __forceinline__ void store_mask(uint8_t* mask, size_t t, unsigned lane, uint32_t m)
     {
         const uint32_t other = swap_with_neighbour(m);
-        const uint32_t byte = (c & 1) ? (((other >> 4) & 0xFu) | (m & 0xF0u))
-                                      : ((m & 0xFu) | ((other & 0xFu) << 4));
-        st_mask(mask + mask_index(c), (uint8_t)byte);
+        const uint32_t byte = (lane & 1) ? (((other >> 4) & 0xFu) | (m & 0xF0u))
+                                         : ((m & 0xFu) | ((other & 0xFu) << 4));
+        st8(tile_buffer(mask, t * kMaskBytes, kMaskBytes), mask_byte(lane), byte);
     }
-    static __device__ __forceinline__ uint32_t load_mask(const uint8_t* mask, size_t c)
+    static __device__ __forceinline__ uint32_t load_mask(const uint8_t* mask, size_t t, unsigned lane)
     {
-        const uint32_t own = ld_mask(mask + mask_index(c));
+        const uint32_t own = ld8(tile_buffer(mask, t * kMaskBytes, kMaskBytes), mask_byte(lane));
         const uint32_t other = swap_with_neighbour(own);
-        return (c & 1) ? ((other >> 4) | (own & 0xF0u)) : ((own & 0xFu) | ((other & 0xFu) << 4));
+        return (lane & 1) ? ((other >> 4) | (own & 0xF0u)) : ((own & 0xFu) | ((other & 0xFu) << 4));
     }
-    static __device__ __forceinline__ float load1(const void* p, size_t i) { return reinterpret_cast<const float*>(p)[i]; }
-    static __device__ __forceinline__ void store1(void* p, size_t i, float v) { reinterpret_cast<float*>(p)[i] = v; }
-    // precision-bit variant: bit 0 of each stored pattern := bit j of m / read it back
-    static __device__ __forceinline__ float tag(float v, uint32_t bit)
-    {
-        return __uint_as_float((__float_as_uint(v) & ~1u) | bit);
-    }
-    static __device__ __forceinline__ uint32_t lsb(float v) { return __float_as_uint(v) & 1u; }
-    static __device__ __forceinline__ void store_tagged(void* p, size_t c, float (&v)[8], uint32_t m)
+    static __device__ __forceinline__ void store_tagged(void* p, size_t t, unsigned lane, float (&v)[8], uint32_t m)
     {
 #pragma unroll
         for (int j = 0; j < 8; ++j) v[j] = tag(v[j], (m >> j) & 1u);
-        store(p, c, v);
+        store(p, t, lane, v);
     }
     static __device__ __forceinline__ uint32_t unpack_tagged(const Raw& r, float (&v)[8])
     {
@@ -247,8 +255,6 @@ template <> struct Storage<INVACT_FP32, 8> {
         for (int j = 0; j < 8; ++j) m |= lsb(v[j]) << j;
         return m;
     }
-    static __device__ __forceinline__ void store1_tagged(void* p, size_t i, float v, bool bit) { store1(p, i, tag(v, bit)); }
-    static __device__ __forceinline__ bool lsb1(const void* p, size_t i) { return lsb(load1(p, i)); }
 };
 
 // bfloat16, 8 elements per lane: one 128-bit access per tensor, and exactly mask byte L of the 512-element wave tile.
@@ -256,10 +262,11 @@ template <> struct Storage<INVACT_BF16, 8> {
     struct Raw { u32x4 w; };
     static constexpr int kPrec = FAST;
     static constexpr int kElems = 8;                    // elements per lane and chunk
-    static constexpr int kWaveTile = 64 * kElems;       // elements per wavefront and tile
-    static __device__ __forceinline__ Raw load(const void* p, size_t c)
+    static constexpr int kWaveTile = kWave * kElems;    // elements per wavefront and tile
+    static constexpr unsigned kTileBytes = kWaveTile * 2, kMaskBytes = kWaveTile / 8;
+    static __device__ __forceinline__ Raw load(const void* p, size_t t, unsigned lane)
     {
-        return Raw{ld(reinterpret_cast<const u32x4*>(p) + c)};
+        return Raw{ld128(tile_buffer(p, t * kTileBytes, kTileBytes), lane * 16)};
     }
     static __device__ __forceinline__ void unpack(const Raw& r, float (&v)[8])
     {
@@ -273,13 +280,19 @@ template <> struct Storage<INVACT_BF16, 8> {
     {
         return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo, hi}, bf16x2));
     }
-    static __device__ __forceinline__ void store(void* p, size_t c, const float (&v)[8])
+    static __device__ __forceinline__ void store(void* p, size_t t, unsigned lane, const float (&v)[8])
     {
-        st(reinterpret_cast<u32x4*>(p) + c,
-           u32x4{pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7])});
+        st128(tile_buffer(p, t * kTileBytes, kTileBytes), lane * 16,
+              u32x4{pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7])});
     }
-    static __device__ __forceinline__ void store_mask(uint8_t* mask, size_t c, uint32_t m) { st_mask(mask + c, (uint8_t)m); }
-    static __device__ __forceinline__ uint32_t load_mask(const uint8_t* mask, size_t c) { return ld_mask(mask + c); }
+    static __device__ __forceinline__ void store_mask(uint8_t* mask, size_t t, unsigned lane, uint32_t m)
+    {
+        st8(tile_buffer(mask, t * kMaskBytes, kMaskBytes), lane, m);
+    }
+    static __device__ __forceinline__ uint32_t load_mask(const uint8_t* mask, size_t t, unsigned lane)
+    {
+        return ld8(tile_buffer(mask, t * kMaskBytes, kMaskBytes), lane);
+    }
     static __device__ __forceinline__ float load1(const void* p, size_t i)
     {
         return __uint_as_float((uint32_t) reinterpret_cast<const uint16_t*>(p)[i] << 16);
@@ -289,7 +302,7 @@ template <> struct Storage<INVACT_BF16, 8> {
         reinterpret_cast<uint16_t*>(p)[i] = (uint16_t)(pack2(v, 0.0f) & 0xFFFFu);
     }
     // precision-bit variant: bit 0 of each stored 16-bit pattern := bit j of m / read it back
-    static __device__ __forceinline__ void store_tagged(void* p, size_t c, float (&v)[8], uint32_t m)
+    static __device__ __forceinline__ void store_tagged(void* p, size_t t, unsigned lane, float (&v)[8], uint32_t m)
     {
         u32x4 w;
 #pragma unroll
@@ -297,7 +310,7 @@ template <> struct Storage<INVACT_BF16, 8> {
             const uint32_t bits = ((m >> (2 * j)) & 1u) | (((m >> (2 * j + 1)) & 1u) << 16);
             w[j] = (pack2(v[2 * j], v[2 * j + 1]) & 0xFFFEFFFEu) | bits;
         }
-        st(reinterpret_cast<u32x4*>(p) + c, w);
+        st128(tile_buffer(p, t * kTileBytes, kTileBytes), lane * 16, w);
     }
     static __device__ __forceinline__ uint32_t unpack_tagged(const Raw& r, float (&v)[8])
     {
@@ -319,8 +332,8 @@ enum MaskMode { MASK_NONE = 0, MASK_WRITE = 1, MASK_READ = 2 };
 // ---------------------------------------------------------------------------
 // The element-wise operations.  Each has
 //   In      -- the raw registers of one chunk of every input stream
-//   load    -- fill In for chunk c
-//   run     -- compute and store chunk c
+//   load    -- fill In for the lane's chunk of wave tile t
+//   run     -- compute and store that chunk
 //   scalar  -- the same for the single element i (tail); takes / returns the mask bit
 // ---------------------------------------------------------------------------
 
@@ -329,8 +342,8 @@ struct FwdOp {                       // y = f(x), s = [x < T]
     using S = Storage<DT, 8>;
     const void* x; void* y; uint8_t* mask;
     struct In { typename S::Raw x; };
-    __device__ __forceinline__ void load(In& in, size_t c) const { in.x = S::load(x, c); }
-    __device__ __forceinline__ void run(const In& in, size_t c) const
+    __device__ __forceinline__ void load(In& in, size_t t, unsigned lane) const { in.x = S::load(x, t, lane); }
+    __device__ __forceinline__ void run(const In& in, size_t t, unsigned lane) const
     {
         float v[S::kElems]; S::unpack(in.x, v);
         uint32_t m = 0;
@@ -339,8 +352,8 @@ struct FwdOp {                       // y = f(x), s = [x < T]
             m |= (uint32_t)(v[j] < KindConst<KIND>::T) << j;
             v[j] = act<KIND, S::kPrec>(v[j]);
         }
-        S::store(y, c, v);
-        S::store_mask(mask, c, m);
+        S::store(y, t, lane, v);
+        S::store_mask(mask, t, lane, m);
     }
     __device__ __forceinline__ bool scalar(size_t i, bool) const
     {
@@ -357,16 +370,16 @@ struct BwdOp {                       // grad_x = grad_y * q(y, s)
     using S = Storage<DT, lean_elems<DT>()>;
     const void* y; const uint8_t* mask; const void* gy; void* gx;
     struct In { typename S::Raw y, g; uint32_t m; };
-    __device__ __forceinline__ void load(In& in, size_t c) const
+    __device__ __forceinline__ void load(In& in, size_t t, unsigned lane) const
     {
-        in.y = S::load(y, c); in.g = S::load(gy, c); in.m = S::load_mask(mask, c);
+        in.y = S::load(y, t, lane); in.g = S::load(gy, t, lane); in.m = S::load_mask(mask, t, lane);
     }
-    __device__ __forceinline__ void run(const In& in, size_t c) const
+    __device__ __forceinline__ void run(const In& in, size_t t, unsigned lane) const
     {
         float a[S::kElems], g[S::kElems]; S::unpack(in.y, a); S::unpack(in.g, g);
 #pragma unroll
         for (int j = 0; j < S::kElems; ++j) g[j] = times_q<KIND, S::kPrec>(g[j], a[j], (in.m >> j) & 1u);
-        S::store(gx, c, g);
+        S::store(gx, t, lane, g);
     }
     __device__ __forceinline__ bool scalar(size_t i, bool bit) const
     {
@@ -382,11 +395,11 @@ struct GluFwdOp {                    // act = f(gate), s = [gate < T], h = f(gat
     using S = Storage<DT, lean_elems<DT>()>;
     const void* gate; const void* up; void* act_out; void* h; uint8_t* mask;
     struct In { typename S::Raw g, u; };
-    __device__ __forceinline__ void load(In& in, size_t c) const
+    __device__ __forceinline__ void load(In& in, size_t t, unsigned lane) const
     {
-        in.g = S::load(gate, c); in.u = S::load(up, c);
+        in.g = S::load(gate, t, lane); in.u = S::load(up, t, lane);
     }
-    __device__ __forceinline__ void run(const In& in, size_t c) const
+    __device__ __forceinline__ void run(const In& in, size_t t, unsigned lane) const
     {
         float v[S::kElems], u[S::kElems]; S::unpack(in.g, v); S::unpack(in.u, u);
         uint32_t m = 0;
@@ -395,9 +408,9 @@ struct GluFwdOp {                    // act = f(gate), s = [gate < T], h = f(gat
             m |= (uint32_t)(v[j] < KindConst<KIND>::T) << j;
             act_times<KIND, S::kPrec>(v[j], u[j], v[j], u[j]);
         }
-        S::store(act_out, c, v);
-        S::store(h, c, u);
-        S::store_mask(mask, c, m);
+        S::store(act_out, t, lane, v);
+        S::store(h, t, lane, u);
+        S::store_mask(mask, t, lane, m);
     }
     __device__ __forceinline__ bool scalar(size_t i, bool) const
     {
@@ -416,11 +429,12 @@ struct GluBwdOp {                    // grad_up = grad_h * act ; grad_gate = gra
     using S = Storage<DT, lean_elems<DT>()>;
     const void* act_in; const void* up; const uint8_t* mask; const void* gh; void* ggate; void* gup;
     struct In { typename S::Raw a, u, g; uint32_t m; };
-    __device__ __forceinline__ void load(In& in, size_t c) const
+    __device__ __forceinline__ void load(In& in, size_t t, unsigned lane) const
     {
-        in.a = S::load(act_in, c); in.u = S::load(up, c); in.g = S::load(gh, c); in.m = S::load_mask(mask, c);
+        in.a = S::load(act_in, t, lane); in.u = S::load(up, t, lane); in.g = S::load(gh, t, lane);
+        in.m = S::load_mask(mask, t, lane);
     }
-    __device__ __forceinline__ void run(const In& in, size_t c) const
+    __device__ __forceinline__ void run(const In& in, size_t t, unsigned lane) const
     {
         float a[S::kElems], u[S::kElems], g[S::kElems]; S::unpack(in.a, a); S::unpack(in.u, u); S::unpack(in.g, g);
 #pragma unroll
@@ -429,8 +443,8 @@ struct GluBwdOp {                    // grad_up = grad_h * act ; grad_gate = gra
             a[j] = g[j] * a[j];                  // grad_up
             u[j] = gate_grad;                    // grad_gate
         }
-        S::store(gup, c, a);
-        S::store(ggate, c, u);
+        S::store(gup, t, lane, a);
+        S::store(ggate, t, lane, u);
     }
     __device__ __forceinline__ bool scalar(size_t i, bool bit) const
     {
@@ -449,8 +463,8 @@ struct PbitFwdOp {                   // y = f(x) with bit 0 := [x < T]
     using S = Storage<DT, 8>;
     const void* x; void* y;
     struct In { typename S::Raw x; };
-    __device__ __forceinline__ void load(In& in, size_t c) const { in.x = S::load(x, c); }
-    __device__ __forceinline__ void run(const In& in, size_t c) const
+    __device__ __forceinline__ void load(In& in, size_t t, unsigned lane) const { in.x = S::load(x, t, lane); }
+    __device__ __forceinline__ void run(const In& in, size_t t, unsigned lane) const
     {
         float v[S::kElems]; S::unpack(in.x, v);
         uint32_t m = 0;
@@ -459,7 +473,7 @@ struct PbitFwdOp {                   // y = f(x) with bit 0 := [x < T]
             m |= (uint32_t)(v[j] < KindConst<KIND>::T) << j;
             v[j] = act<KIND, S::kPrec>(v[j]);
         }
-        S::store_tagged(y, c, v, m);
+        S::store_tagged(y, t, lane, v, m);
     }
     __device__ __forceinline__ bool scalar(size_t i, bool) const
     {
@@ -476,15 +490,18 @@ struct PbitBwdOp {                   // s = bit 0 of y; grad_x = grad_y * q(y, s
     using S = Storage<DT, lean_elems<DT>()>;
     const void* y; const void* gy; void* gx;
     struct In { typename S::Raw y, g; };
-    __device__ __forceinline__ void load(In& in, size_t c) const { in.y = S::load(y, c); in.g = S::load(gy, c); }
-    __device__ __forceinline__ void run(const In& in, size_t c) const
+    __device__ __forceinline__ void load(In& in, size_t t, unsigned lane) const
+    {
+        in.y = S::load(y, t, lane); in.g = S::load(gy, t, lane);
+    }
+    __device__ __forceinline__ void run(const In& in, size_t t, unsigned lane) const
     {
         float a[S::kElems], g[S::kElems];
         const uint32_t m = S::unpack_tagged(in.y, a);
         S::unpack(in.g, g);
 #pragma unroll
         for (int j = 0; j < S::kElems; ++j) g[j] = times_q<KIND, S::kPrec>(g[j], a[j], (m >> j) & 1u);
-        S::store(gx, c, g);
+        S::store(gx, t, lane, g);
     }
     __device__ __forceinline__ bool scalar(size_t i, bool) const
     {
@@ -495,20 +512,20 @@ struct PbitBwdOp {                   // s = bit 0 of y; grad_x = grad_y * q(y, s
     static constexpr Shape kShape = pick<DT>({1, 24}, {1, 32});   // {tiles, resident cap}: binary32, bfloat16
 };
 
-// Sign-bit variant: no mask tensor and an exact forward; the saved tensor is f(x) - min f, which is
-// never negative, with the indicator in its sign bit.  Whoever consumes it adds the minimum back.
+// Sign-bit variant: no mask tensor; the saved tensor is f(x) - min f, which is never negative, with
+// the indicator in its sign bit.  Whoever consumes it adds the minimum back.
 template <int KIND, int DT>
 struct SbitFwdOp {                   // y_tagged = +-(f(x) - C), sign bit := [x < T]
     using S = Storage<DT, 8>;
     const void* x; void* yt;
     struct In { typename S::Raw x; };
-    __device__ __forceinline__ void load(In& in, size_t c) const { in.x = S::load(x, c); }
-    __device__ __forceinline__ void run(const In& in, size_t c) const
+    __device__ __forceinline__ void load(In& in, size_t t, unsigned lane) const { in.x = S::load(x, t, lane); }
+    __device__ __forceinline__ void run(const In& in, size_t t, unsigned lane) const
     {
         float v[S::kElems]; S::unpack(in.x, v);
 #pragma unroll
         for (int j = 0; j < S::kElems; ++j) v[j] = act_minus_min_signed<KIND, S::kPrec>(v[j]);
-        S::store(yt, c, v);
+        S::store(yt, t, lane, v);
     }
     __device__ __forceinline__ bool scalar(size_t i, bool) const
     {
@@ -524,13 +541,13 @@ struct SbitDecodeOp {                // y = |y_tagged| + C
     using S = Storage<DT, lean_elems<DT>()>;
     const void* yt; void* y;
     struct In { typename S::Raw y; };
-    __device__ __forceinline__ void load(In& in, size_t c) const { in.y = S::load(yt, c); }
-    __device__ __forceinline__ void run(const In& in, size_t c) const
+    __device__ __forceinline__ void load(In& in, size_t t, unsigned lane) const { in.y = S::load(yt, t, lane); }
+    __device__ __forceinline__ void run(const In& in, size_t t, unsigned lane) const
     {
         float v[S::kElems]; S::unpack(in.y, v);
 #pragma unroll
         for (int j = 0; j < S::kElems; ++j) v[j] = fabsf(v[j]) + KindConst<KIND>::fT;
-        S::store(y, c, v);
+        S::store(y, t, lane, v);
     }
     __device__ __forceinline__ bool scalar(size_t i, bool) const
     {
@@ -546,19 +563,22 @@ struct SbitBwdOp {                   // s = sign bit of y_tagged; grad_x = grad_
     using S = Storage<DT, lean_elems<DT>()>;
     const void* yt; const void* gy; void* gx;
     struct In { typename S::Raw y, g; };
-    __device__ __forceinline__ void load(In& in, size_t c) const { in.y = S::load(yt, c); in.g = S::load(gy, c); }
+    __device__ __forceinline__ void load(In& in, size_t t, unsigned lane) const
+    {
+        in.y = S::load(yt, t, lane); in.g = S::load(gy, t, lane);
+    }
     static __device__ __forceinline__ float one(float g, float t)
     {
         return times_q<KIND, S::kPrec>(g, fabsf(t) + KindConst<KIND>::fT, (__float_as_uint(t) >> 31) != 0);
     }
-    __device__ __forceinline__ void run(const In& in, size_t c) const
+    __device__ __forceinline__ void run(const In& in, size_t t, unsigned lane) const
     {
         float a[S::kElems], g[S::kElems];
         S::unpack(in.y, a);
         S::unpack(in.g, g);
 #pragma unroll
         for (int j = 0; j < S::kElems; ++j) g[j] = one(g[j], a[j]);
-        S::store(gx, c, g);
+        S::store(gx, t, lane, g);
     }
     __device__ __forceinline__ bool scalar(size_t i, bool) const
     {
@@ -573,70 +593,68 @@ struct SbitBwdOp {                   // s = sign bit of y_tagged; grad_x = grad_
 // Skeleton
 // ---------------------------------------------------------------------------
 
-// PERSISTENT: the grid strides over the chunks (a fixed number of workgroups
-// per compute unit).  Otherwise every workgroup handles one tile of
-// kUnroll * kThreads chunks and retires, and the dispatcher balances the load.
-// The number of chunks is a multiple of 64, so a wavefront is either entirely
-// inside the tensor or entirely outside: every branch below is wave-uniform
-// (the neighbour swap of the binary32 mask needs whole quads).
+// A workgroup is one wavefront.  PERSISTENT: the grid strides over the wave
+// tiles (a fixed number of workgroups per compute unit).  Otherwise every
+// workgroup handles kUnroll consecutive wave tiles and retires, and the
+// dispatcher balances the load.  The tile index comes from the workgroup index,
+// so every branch below is wave-uniform (the neighbour swap of the binary32
+// mask needs whole quads) and tile addresses stay in scalar registers.
 template <class Op, bool PERSISTENT>
-__global__ __launch_bounds__(Op::kShape.threads) void stream_kernel(const Op op, const size_t n)
+__global__ __launch_bounds__(kWave) void stream_kernel(const Op op, const size_t n)
 {
-    constexpr int kThreads = Op::kShape.threads;
     constexpr int kUnroll = Op::kShape.unroll;
     constexpr size_t kWaveTile = Op::S::kWaveTile;
     const size_t wave_tiles = n / kWaveTile;
-    const size_t chunks = wave_tiles * 64;
+    const unsigned lane = threadIdx.x;
 
     if constexpr (PERSISTENT) {
-        const size_t stride = (size_t)gridDim.x * kThreads;
-        size_t c = (size_t)blockIdx.x * kThreads + threadIdx.x;
-        for (; c + (kUnroll - 1) * stride < chunks; c += kUnroll * stride) {
+        const size_t stride = gridDim.x;
+        size_t t = blockIdx.x;
+        for (; t + (kUnroll - 1) * stride < wave_tiles; t += kUnroll * stride) {
             typename Op::In in[kUnroll];
 #pragma unroll
-            for (int u = 0; u < kUnroll; ++u) op.load(in[u], c + u * stride);
+            for (int u = 0; u < kUnroll; ++u) op.load(in[u], t + u * stride, lane);
 #pragma unroll
-            for (int u = 0; u < kUnroll; ++u) op.run(in[u], c + u * stride);
+            for (int u = 0; u < kUnroll; ++u) op.run(in[u], t + u * stride, lane);
         }
-        for (; c < chunks; c += stride) {
+        for (; t < wave_tiles; t += stride) {
             typename Op::In in;
-            op.load(in, c);
-            op.run(in, c);
+            op.load(in, t, lane);
+            op.run(in, t, lane);
         }
     } else {
-        const size_t c = (size_t)blockIdx.x * (kThreads * kUnroll) + threadIdx.x;
-        if (c + (kUnroll - 1) * kThreads < chunks) {
+        const size_t t = (size_t)blockIdx.x * kUnroll;
+        if (t + kUnroll <= wave_tiles) {
             typename Op::In in[kUnroll];
 #pragma unroll
-            for (int u = 0; u < kUnroll; ++u) op.load(in[u], c + u * kThreads);
+            for (int u = 0; u < kUnroll; ++u) op.load(in[u], t + u, lane);
 #pragma unroll
-            for (int u = 0; u < kUnroll; ++u) op.run(in[u], c + u * kThreads);
+            for (int u = 0; u < kUnroll; ++u) op.run(in[u], t + u, lane);
         } else {
             for (int u = 0; u < kUnroll; ++u) {
-                const size_t cu = c + u * kThreads;
-                if (cu < chunks) {
+                if (t + u < wave_tiles) {
                     typename Op::In in;
-                    op.load(in, cu);
-                    op.run(in, cu);
+                    op.load(in, t + u, lane);
+                    op.run(in, t + u, lane);
                 }
             }
         }
     }
 
-    // Tail: elements [512 wave_tiles, n), one per lane, by the first wavefront.
+    // Tail: elements [kWaveTile wave_tiles, n), one per lane, by the first wavefront.
     // Whole 64-bit mask words are written (read), so the zero padding of the
     // last word comes from the ballot itself.
-    if (blockIdx.x == 0 && threadIdx.x < 64) {
+    if (blockIdx.x == 0) {
         for (size_t base = wave_tiles * kWaveTile; base < n; base += 64) {
-            const size_t i = base + threadIdx.x;
+            const size_t i = base + lane;
             if constexpr (Op::kMask == MASK_WRITE) {
                 bool bit = false;
                 if (i < n) bit = op.scalar(i, false);
                 const uint64_t word = __builtin_amdgcn_ballot_w64(bit);
-                if (threadIdx.x == 0) reinterpret_cast<uint64_t*>(op.mask)[base / 64] = word;
+                if (lane == 0) reinterpret_cast<uint64_t*>(op.mask)[base / 64] = word;
             } else if constexpr (Op::kMask == MASK_READ) {
                 const uint64_t word = reinterpret_cast<const uint64_t*>(op.mask)[base / 64];
-                if (i < n) op.scalar(i, (word >> threadIdx.x) & 1u);
+                if (i < n) op.scalar(i, (word >> lane) & 1u);
             } else {
                 if (i < n) op.scalar(i, false);
             }
@@ -673,7 +691,7 @@ bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) &
 template <class Op>
 unsigned occupancy_cap_lds(int resident)
 {
-    if (resident <= 0 || resident * (Op::kShape.threads / 64) >= kWaveSlotsPerCu) return 0;   // the hardware's own limit
+    if (resident <= 0 || resident >= kWaveSlotsPerCu) return 0;   // the hardware's own limit
     static std::atomic<uint64_t> prepared{0};
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
@@ -688,28 +706,37 @@ unsigned occupancy_cap_lds(int resident)
     return kLdsPerCu / (unsigned)resident;
 }
 
+// Enqueues one launch and reports THIS launch's status: the runtime's return value, not the
+// thread's last-error slot, which may still hold (and would clear) an error of the caller's own work.
+template <class Op>
+int enqueue(void (*kernel)(Op, size_t), unsigned blocks, unsigned threads, unsigned lds, hipStream_t stream,
+            Op op, size_t n)
+{
+    void* args[] = {&op, &n};
+    return hipLaunchKernel(reinterpret_cast<const void*>(kernel), dim3(blocks), dim3(threads), args, lds, stream)
+               == hipSuccess ? INVACT_OK : INVACT_ERR_HIP;
+}
+
 template <class Op>
 int launch(const Op& op, size_t n, hipStream_t stream)
 {
     constexpr int kUnroll = Op::kShape.unroll;
-    constexpr int kThreads = Op::kShape.threads;
-    const size_t chunks = (n / Op::S::kWaveTile) * 64;
+    const size_t wave_tiles = n / Op::S::kWaveTile;
     const int per_cu = g_blocks_per_cu.load(std::memory_order_relaxed);
     if (per_cu == 0) {
-        size_t blocks = (chunks + kThreads * kUnroll - 1) / (kThreads * kUnroll);
-        if (blocks == 0) blocks = 1;                          // the tail still needs a thread
+        size_t blocks = (wave_tiles + kUnroll - 1) / kUnroll;
+        if (blocks == 0) blocks = 1;                          // the tail still needs a wavefront
         if (blocks > 0x7FFFFFFFu) return INVACT_ERR_SIZE;
         const int forced = g_resident_override.load(std::memory_order_relaxed);
         const unsigned lds = occupancy_cap_lds<Op>(forced ? forced : Op::kShape.resident);
-        hipLaunchKernelGGL((stream_kernel<Op, false>), dim3((unsigned)blocks), dim3(kThreads), lds, stream, op, n);
+        return enqueue(stream_kernel<Op, false>, (unsigned)blocks, kWave, lds, stream, op, n);
     } else {
-        size_t blocks = (chunks + kThreads - 1) / kThreads;
+        size_t blocks = wave_tiles;
         const size_t cap = (size_t)cu_count() * (size_t)per_cu;
         if (blocks > cap) blocks = cap;
         if (blocks == 0) blocks = 1;
-        hipLaunchKernelGGL((stream_kernel<Op, true>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, op, n);
+        return enqueue(stream_kernel<Op, true>, (unsigned)blocks, kWave, 0, stream, op, n);
     }
-    return hipGetLastError() == hipSuccess ? INVACT_OK : INVACT_ERR_HIP;
 }
 
 // Runs fn<KIND, DT>() for the run-time (kind, dtype) pair.

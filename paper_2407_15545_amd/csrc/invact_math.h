@@ -157,8 +157,9 @@ __device__ __forceinline__ double act_precise(float x)
     return fmax((double)x, -0.0) - fabs(u);
 }
 
-// The clamps above drop a NaN; put it back.
-__device__ __forceinline__ float nan_through(float x, float v) { return (x != x) ? x : v; }
+// The clamps above drop a NaN; put it back, as a quiet one: the precision-bit variant clears bit 0 of
+// the stored pattern, which would turn the signalling NaNs 0x7F800001 / 0xFF800001 into infinities.
+__device__ __forceinline__ float nan_through(float x, float v) { return (x != x) ? __uint_as_float(0x7FC00000u) : v; }
 
 // f(x) rounded once to binary32.
 template <int KIND, int PREC>

@@ -17,7 +17,7 @@ import sys
 import numpy as np
 import torch
 
-from paper_2407_15545_amd import synth
+import synth
 
 P_BITS = {"fp32": 24, "bf16": 8}
 TORCH_DTYPE = {"fp32": torch.float32, "bf16": torch.bfloat16}

@@ -12,7 +12,7 @@ import torch
 import oracle as O
 import parity as PT
 from paper_2407_15545_amd import binding as B
-from paper_2407_15545_amd import synth
+import synth
 
 pytestmark = pytest.mark.gpu
 KINDS = ["gelu_tanh", "gelu_erf", "silu"]
@@ -94,3 +94,20 @@ def test_pbit_in_place(dtype):
     torch.cuda.synchronize()
     assert torch.equal(x2.view(torch.uint8), y.view(torch.uint8))
     assert torch.equal(g2.view(torch.uint8), gx.view(torch.uint8))
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_pbit_nan_inputs_stay_nan_in_binary32(kind):
+    """Clearing bit 0 of the signalling NaNs 0x7F800001 / 0xFF800001 would leave an infinity: the forward
+    must store a NaN for every NaN input, and the backward must give NaN for it (the oracle does both)."""
+    pats = np.array([0x7F800001, 0xFF800001, 0x7FC00000, 0xFFC00001, 0x7FFFFFFF, 0x7F800002] * 100, dtype=np.uint32)
+    x = torch.from_numpy(pats.view(np.int32)).cuda().view(torch.float32)
+    ye, ys = O.pbit_fwd(kind, "fp32", np.full(pats.size, np.nan))
+    assert np.all(np.isnan(ys))
+    PT.say(f"invact_pbit_fwd {kind} fp32 NaN patterns")
+    y = B.invact_pbit_fwd(kind, x)
+    gx = B.invact_pbit_bwd(kind, y, torch.ones_like(y))
+    torch.cuda.synchronize()
+    assert torch.isnan(y).all(), patterns(y)[:6]
+    assert torch.isnan(gx).all()
+    assert np.all(np.isnan(O.pbit_bwd(kind, "fp32", ys, np.ones(pats.size))))

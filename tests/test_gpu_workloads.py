@@ -18,7 +18,7 @@ import torch
 import oracle as O
 import parity as PT
 from paper_2407_15545_amd import binding as B
-from paper_2407_15545_amd import synth
+import synth
 
 pytestmark = pytest.mark.gpu
 REPORT_DIR = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")

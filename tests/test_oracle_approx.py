@@ -21,7 +21,7 @@ import numpy as np
 import pytest
 
 import oracle as O
-from paper_2407_15545_amd import synth
+import synth
 
 KINDS = ["gelu_tanh", "gelu_erf", "silu"]
 KID = O.KINDS

@@ -16,7 +16,7 @@ import scipy.stats
 import torch
 
 import oracle as O
-from paper_2407_15545_amd import synth
+import synth
 
 KINDS = ["gelu_tanh", "gelu_erf", "silu"]
 mp.mp.dps = 40

@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 
 import oracle as O
-from paper_2407_15545_amd import synth
+import synth
 
 KINDS = ["gelu_tanh", "gelu_erf", "silu"]
 
@@ -79,3 +79,12 @@ def test_backward_reads_the_bit_and_uses_the_stored_value(kind, dtype):
     _, plain, m = O.invact_fwd(kind, dtype, x)
     ref = O.invact_bwd(kind, plain, m, g)
     assert np.max(np.abs(gx - ref)) <= (4e-2 if dtype == "bf16" else 1e-3) * np.max(np.abs(g))
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("kind", KINDS)
+def test_a_nan_stays_a_nan_through_the_tag(kind, dtype):
+    """The indicator of a NaN is 0 and clearing the lowest bit must not turn it into an infinity."""
+    ye, ys = O.pbit_fwd(kind, dtype, np.array([np.nan, -np.nan]))
+    assert np.all(np.isnan(ye)) and np.all(np.isnan(ys))
+    assert np.all(np.isnan(O.pbit_bwd(kind, dtype, ys, np.ones(2))))

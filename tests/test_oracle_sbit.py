@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 
 import oracle as O
-from paper_2407_15545_amd import synth
+import synth
 
 KINDS = ["gelu_tanh", "gelu_erf", "silu"]
 P = {"fp32": 24, "bf16": 8}

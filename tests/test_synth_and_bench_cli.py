@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 import torch
 
-from paper_2407_15545_amd import synth
+import synth
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -85,3 +85,19 @@ def test_bench_refuses_more_than_one_gpu():
                          capture_output=True, text=True, timeout=120)
     assert res.returncode != 0
     assert "one GPU" in res.stderr and res.stdout.strip() == ""
+
+
+def test_bench_takes_its_traffic_figure_from_the_committed_profile():
+    """`roofline.traffic` is the HBM byte count of the rocprofv3 counter runs summarised under profiles/:
+    bench.py reads it from there, and the figure must be the sum of that file's own read and write columns."""
+    import re
+    sys.path.insert(0, ROOT)
+    import bench
+    text = open(os.path.join(ROOT, bench.PROFILE)).read()
+    row = re.search(r"^\| swiglu_invact_bwd \| ([0-9.]+) \| ([0-9.]+) \| ([0-9.]+) \| ([0-9.]+) \|", text, re.M)
+    assert row, "the profile's traffic table has no backward row"
+    read_mb, write_mb, total_mb, algorithmic_mb = map(float, row.groups())
+    assert abs(read_mb + write_mb - total_mb) < 0.11
+    assert bench.profiled_traffic() == pytest.approx(total_mb * 1e6, rel=1e-4)
+    assert algorithmic_mb == pytest.approx(synth.numel(bench.WORKLOAD) * bench.BYTES_BWD / 1e6, rel=1e-4)
+    assert 1.0 <= total_mb / algorithmic_mb < 1.05        # no wasted re-reads to speak of
