@@ -148,7 +148,7 @@ def entry_sweep(args):
                              c=torch.randn(n, device="cuda").to(td), o1=torch.empty(n, device="cuda", dtype=td),
                              o2=torch.empty(n, device="cuda", dtype=td),
                              mask=torch.empty(B.mask_bytes(n), dtype=torch.uint8, device="cuda")) for _ in range(sets)]
-                launches = max(sets, min(200, (1 << 31) // (n * width)))
+                launches = max(sets, 20, min(400, (1 << 35) // (n * width)))   # 30 ms or more per group
                 for kind in args.kinds:
                     for s in bufs:                                         # valid saved tensors for the backward calls
                         s["y"], s["ymask"] = B.invact_fwd(kind, s["a"])
@@ -190,10 +190,8 @@ def entry_sweep(args):
                                     g.replay()
                                     ms = group_ms(torch, stream, g.replay, 1, 3)[0] / launches
                                 else:
-                                    for _ in range(min(3, sets)):
-                                        launch()
-                                    torch.cuda.synchronize()
-                                    ms = group_ms(torch, stream, launch, launches, 3)[0]
+                                    group_ms(torch, stream, launch, launches, 1)       # untimed: clocks, TLBs
+                                    ms = group_ms(torch, stream, launch, launches, 5)[0]
                                 gbs = n * ENTRY_BYTES[entry][0 if dt == "fp32" else 1] / ms / 1e6
                                 note = ("launch-bound" if n < (1 << 24) else "") + (" graph" if args.graph else "")
                                 print(f"{tag} {entry:18s} {kind:9s} {dt} n={n:<10d} sets={sets:<2d} bpc={bpc:<2d} res={res:<2d} "

@@ -13,8 +13,9 @@ imported from or shared with it.
   * The cubic exponent c3 (c4 - y~)^3 log2(e) of Eqs. (6) and (8) expanded in
     powers of y~ (all four terms have the same sign, so Horner's rule in
     binary32 loses nothing and needs one rounding fewer near y~ = 0).
-  * Polynomial fits of erfcx(z) = exp(z^2) erfc(z) in w = 1 / (1 + p z), used
-    by the erf form of GELU:  erfcx(z) ~ w * sum_k a_k w^k on z in [0, 10].
+  * A polynomial fit of erfcx(z) = exp(z^2) erfc(z) in w = 1 / (1 + p z), used
+    by the erf form of GELU with bfloat16 storage:  erfcx(z) ~ w * sum_k a_k w^k on z in [0, 10];
+    for binary32 storage a table of degree-4 polynomials of erfcx(x / sqrt 2) / 2 on intervals of width 1/8.
   * A polynomial fit of 2^f on |f| <= 0.501 for the binary32-storage forward
     (the hardware exponential's 0.78 ulp would be the largest error there).
 """
@@ -59,6 +60,26 @@ def erfcx_fit(p, deg, zmax=10.0):
     ww = 1 / (1 + p * zz)
     err = np.abs(P.polyval(ww, mono) * ww / sp.erfcx(zz) - 1).max()
     return mono, err
+
+
+def mills_table(rows, per_unit, deg):
+    """G(x) = Phi(-x) exp(x^2 / 2) = erfcx(x / sqrt 2) / 2 on [0, rows / per_unit) as one polynomial per interval
+    of width 1 / per_unit: row i holds the monomial coefficients in t = per_unit x - i in [0, 1).
+    Returns (coefficients [rows][deg + 1], max relative error)."""
+    G = lambda x: 0.5 * sp.erfcx(x / np.sqrt(2.0))
+    k = np.arange(4 * deg + 8)
+    node = np.cos(np.pi * (k + 0.5) / k.size)                  # Chebyshev nodes on [-1, 1]; t = (node + 1) / 2
+    table, worst = [], 0.0
+    for i in range(rows):
+        cheb = C.chebfit(node, G((i + 0.5 * (node + 1)) / per_unit), deg)
+        mono, pw = np.zeros(1), np.ones(1)
+        for ck in C.cheb2poly(cheb):                           # node = 2 t - 1
+            mono = P.polyadd(mono, ck * pw)
+            pw = P.polymul(pw, np.array([-1.0, 2.0]))
+        tt = np.linspace(0.0, 1.0, 4001)
+        worst = max(worst, np.abs(P.polyval(tt, mono) / G((i + tt) / per_unit) - 1).max())
+        table.append(mono)
+    return table, worst
 
 
 def exp2_fit(deg, half=0.501):
@@ -114,15 +135,23 @@ def main():
     out.append(arr("gelu_right_exp2", cubic(GELU_RIGHT[3], GELU_RIGHT[4])))
     out.append(arr("silu_right_exp2", cubic(SILU_RIGHT[3], SILU_RIGHT[4])))
     out.append("")
-    # degree 4: 3.4e-5 is under 2 % of half a bfloat16 ulp, and every fma less shows in the forward's speed
-    mono, err = erfcx_fit(0.53, 4)
-    out.append(f"// erfcx(z) ~ w (a0 + a1 w + ... ), w = 1/(1 + {0.53} z); max rel. error {err:.2e} on [0, 10]")
-    out.append("static constexpr float erfcx_fast_p = 0.53f;")
+    # degree 3: 2.6e-4 is 13 % of half a bfloat16 ulp (the stored value stays within 0.57 ulp of f(x)),
+    # and every fma less shows in the speed of the bfloat16 forward
+    mono, err = erfcx_fit(0.42, 3)
+    out.append(f"// erfcx(z) ~ w (a0 + a1 w + ... ), w = 1/(1 + {0.42} z); max rel. error {err:.2e} on [0, 10]")
+    out.append("static constexpr float erfcx_fast_p = 0.42f;")
     out.append(arr("erfcx_fast", mono))
-    mono, err = erfcx_fit(0.42, 9)
-    out.append(f"// same form in double, w = 1/(1 + {0.42} z); max rel. error {err:.2e} on [0, 10]")
-    out.append("static constexpr double erfcx_precise_p = 0.42;")
-    out.append(arr("erfcx_precise", mono, "double", ""))
+    # binary32 storage: erfcx from a table of short polynomials (held in LDS by the kernels): 116 intervals of
+    # width 1/8 cover every |x| whose result is not yet +-0 or x itself in binary32
+    rows, per_unit, deg = 116, 8, 4
+    table, err = mills_table(rows, per_unit, deg)
+    out.append(f"// Phi(-x) exp(x^2/2) on [{0}, {rows / per_unit}): row i = coefficients in t = {per_unit} x - i of a degree-{deg} fit "
+               f"on [i/{per_unit}, (i+1)/{per_unit}); max rel. error {err:.2e}")
+    out.append(f"static constexpr int mills_rows = {rows}, mills_cols = {deg + 1}, mills_per_unit = {per_unit};")
+    out.append(f"#define INVACT_MILLS_TABLE \\")
+    for i, row in enumerate(table):
+        out.append("    " + ", ".join(f"{v:.17g}" for v in row) + ("," if i + 1 < rows else "") + " \\")
+    out.append("")
     mono, err = exp2_fit(6)
     out.append(f"// 2^f ~ e0 + e1 f + ... on |f| <= 0.501; max rel. error {err:.2e}")
     out.append(arr("exp2_precise", mono, "double", ""))

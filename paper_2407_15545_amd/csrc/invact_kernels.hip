@@ -327,6 +327,23 @@ template <> struct Storage<INVACT_BF16, 8> {
     static __device__ __forceinline__ bool lsb1(const void* p, size_t i) { return reinterpret_cast<const uint16_t*>(p)[i] & 1u; }
 };
 
+// The indicator [x < T] of all elements of a chunk, packed (element j -> bit j), without compares and
+// selects: (T - x) 2^25 is at least 2 for every binary32 x below T (T lies in [-2, -1/2], where
+// neighbouring values are at least 2^-24 apart) and at most 0 otherwise, so clamping it to [0, 1] gives
+// exactly 1.0 or 0.0 -- a fused multiply-add with the clamp modifier, which also turns a NaN into 0 and
+// -inf into 1 -- and sum_j 2^j [x_j < T] is exact in binary32.  Two full-rate instructions per element
+// instead of compare + select + or.
+template <int KIND, int N>
+__device__ __forceinline__ uint32_t indicator_bits(const float (&v)[N])
+{
+    constexpr float kBig = 33554432.0f;                                // 2^25
+    float sum = med3(fmaf(v[0], -kBig, KindConst<KIND>::T * kBig), 0.0f, 1.0f);
+#pragma unroll
+    for (int j = 1; j < N; ++j)
+        sum = fmaf(med3(fmaf(v[j], -kBig, KindConst<KIND>::T * kBig), 0.0f, 1.0f), (float)(1u << j), sum);
+    return (uint32_t)sum;
+}
+
 enum MaskMode { MASK_NONE = 0, MASK_WRITE = 1, MASK_READ = 2 };
 
 // ---------------------------------------------------------------------------
@@ -346,12 +363,9 @@ struct FwdOp {                       // y = f(x), s = [x < T]
     __device__ __forceinline__ void run(const In& in, size_t t, unsigned lane) const
     {
         float v[S::kElems]; S::unpack(in.x, v);
-        uint32_t m = 0;
+        const uint32_t m = indicator_bits<KIND>(v);
 #pragma unroll
-        for (int j = 0; j < S::kElems; ++j) {
-            m |= (uint32_t)(v[j] < KindConst<KIND>::T) << j;
-            v[j] = act<KIND, S::kPrec>(v[j]);
-        }
+        for (int j = 0; j < S::kElems; ++j) v[j] = act<KIND, S::kPrec>(v[j]);
         S::store(y, t, lane, v);
         S::store_mask(mask, t, lane, m);
     }
@@ -362,6 +376,7 @@ struct FwdOp {                       // y = f(x), s = [x < T]
         return v < KindConst<KIND>::T;
     }
     static constexpr int kMask = MASK_WRITE;
+    static constexpr bool kMillsTable = KIND == GELU_ERF && S::kPrec == PRECISE   /* erfcx comes from the LDS table */;
     static constexpr Shape kShape = pick<DT>({2, 32}, {1, 32});   // {tiles, resident cap}: binary32, bfloat16
 };
 
@@ -387,6 +402,7 @@ struct BwdOp {                       // grad_x = grad_y * q(y, s)
         return bit;
     }
     static constexpr int kMask = MASK_READ;
+    static constexpr bool kMillsTable = false;
     static constexpr Shape kShape = pick<DT>({1, 24}, {1, 32});   // {tiles, resident cap}: binary32, bfloat16
 };
 
@@ -402,12 +418,9 @@ struct GluFwdOp {                    // act = f(gate), s = [gate < T], h = f(gat
     __device__ __forceinline__ void run(const In& in, size_t t, unsigned lane) const
     {
         float v[S::kElems], u[S::kElems]; S::unpack(in.g, v); S::unpack(in.u, u);
-        uint32_t m = 0;
+        const uint32_t m = indicator_bits<KIND>(v);
 #pragma unroll
-        for (int j = 0; j < S::kElems; ++j) {
-            m |= (uint32_t)(v[j] < KindConst<KIND>::T) << j;
-            act_times<KIND, S::kPrec>(v[j], u[j], v[j], u[j]);
-        }
+        for (int j = 0; j < S::kElems; ++j) act_times<KIND, S::kPrec>(v[j], u[j], v[j], u[j]);
         S::store(act_out, t, lane, v);
         S::store(h, t, lane, u);
         S::store_mask(mask, t, lane, m);
@@ -421,6 +434,7 @@ struct GluFwdOp {                    // act = f(gate), s = [gate < T], h = f(gat
         return v < KindConst<KIND>::T;
     }
     static constexpr int kMask = MASK_WRITE;
+    static constexpr bool kMillsTable = KIND == GELU_ERF && S::kPrec == PRECISE   /* erfcx comes from the LDS table */;
     static constexpr Shape kShape = pick<DT>({1, 16}, {1, 16});   // {tiles, resident cap}: binary32, bfloat16
 };
 
@@ -454,6 +468,7 @@ struct GluBwdOp {                    // grad_up = grad_h * act ; grad_gate = gra
         return bit;
     }
     static constexpr int kMask = MASK_READ;
+    static constexpr bool kMillsTable = false;
     static constexpr Shape kShape = pick<DT>({1, 16}, {1, 16});   // {tiles, resident cap}: binary32, bfloat16
 };
 
@@ -467,12 +482,9 @@ struct PbitFwdOp {                   // y = f(x) with bit 0 := [x < T]
     __device__ __forceinline__ void run(const In& in, size_t t, unsigned lane) const
     {
         float v[S::kElems]; S::unpack(in.x, v);
-        uint32_t m = 0;
+        const uint32_t m = indicator_bits<KIND>(v);
 #pragma unroll
-        for (int j = 0; j < S::kElems; ++j) {
-            m |= (uint32_t)(v[j] < KindConst<KIND>::T) << j;
-            v[j] = act<KIND, S::kPrec>(v[j]);
-        }
+        for (int j = 0; j < S::kElems; ++j) v[j] = act<KIND, S::kPrec>(v[j]);
         S::store_tagged(y, t, lane, v, m);
     }
     __device__ __forceinline__ bool scalar(size_t i, bool) const
@@ -482,6 +494,7 @@ struct PbitFwdOp {                   // y = f(x) with bit 0 := [x < T]
         return false;
     }
     static constexpr int kMask = MASK_NONE;
+    static constexpr bool kMillsTable = KIND == GELU_ERF && S::kPrec == PRECISE   /* erfcx comes from the LDS table */;
     static constexpr Shape kShape = pick<DT>({2, 32}, {1, 32});   // {tiles, resident cap}: binary32, bfloat16
 };
 
@@ -509,6 +522,7 @@ struct PbitBwdOp {                   // s = bit 0 of y; grad_x = grad_y * q(y, s
         return false;
     }
     static constexpr int kMask = MASK_NONE;
+    static constexpr bool kMillsTable = false;
     static constexpr Shape kShape = pick<DT>({1, 24}, {1, 32});   // {tiles, resident cap}: binary32, bfloat16
 };
 
@@ -533,6 +547,7 @@ struct SbitFwdOp {                   // y_tagged = +-(f(x) - C), sign bit := [x 
         return false;
     }
     static constexpr int kMask = MASK_NONE;
+    static constexpr bool kMillsTable = KIND == GELU_ERF && S::kPrec == PRECISE   /* erfcx comes from the LDS table */;
     static constexpr Shape kShape = pick<DT>({2, 32}, {1, 32});   // {tiles, resident cap}: binary32, bfloat16
 };
 
@@ -555,6 +570,7 @@ struct SbitDecodeOp {                // y = |y_tagged| + C
         return false;
     }
     static constexpr int kMask = MASK_NONE;
+    static constexpr bool kMillsTable = false;
     static constexpr Shape kShape = pick<DT>({2, 20}, {1, 32});   // {tiles, resident cap}: binary32, bfloat16
 };
 
@@ -586,6 +602,7 @@ struct SbitBwdOp {                   // s = sign bit of y_tagged; grad_x = grad_
         return false;
     }
     static constexpr int kMask = MASK_NONE;
+    static constexpr bool kMillsTable = false;
     static constexpr Shape kShape = pick<DT>({1, 24}, {1, 32});   // {tiles, resident cap}: binary32, bfloat16
 };
 
@@ -606,6 +623,7 @@ __global__ __launch_bounds__(kWave) void stream_kernel(const Op op, const size_t
     constexpr size_t kWaveTile = Op::S::kWaveTile;
     const size_t wave_tiles = n / kWaveTile;
     const unsigned lane = threadIdx.x;
+    if constexpr (Op::kMillsTable) fill_mills_table(lane);
 
     if constexpr (PERSISTENT) {
         const size_t stride = gridDim.x;
@@ -703,7 +721,8 @@ unsigned occupancy_cap_lds(int resident)
         }
         prepared.fetch_or(uint64_t(1) << dev, std::memory_order_release);
     }
-    return kLdsPerCu / (unsigned)resident;
+    const unsigned share = kLdsPerCu / (unsigned)resident, own = Op::kMillsTable ? (unsigned)kMillsTableBytes : 0u;
+    return share > own ? share - own : 0;
 }
 
 // Enqueues one launch and reports THIS launch's status: the runtime's return value, not the

@@ -4,12 +4,12 @@
 //   FAST    -- binary32 throughout, hardware exp2 / rcp / sqrt (each within one
 //              ulp) and short polynomials; far more accurate than a bfloat16
 //              store can show.  Used when the storage dtype is bfloat16.
-//   PRECISE -- arguments and the final combination in binary64 (full rate on
-//              this chip), the transcendental itself still the binary32 unit,
-//              fed with the fractional part of a hi + lo split argument; one
-//              rounding to binary32 at the end.  Used when the storage dtype is
-//              binary32, where a binary32 exponent argument alone would cost
-//              5-70 ulp in the left tail.
+//   PRECISE -- everything up to one final rounding in binary64 (a little over half
+//              the binary32 rate on this chip): 2^t from an exact split of t and a
+//              polynomial, reciprocals from a binary32 seed and one Newton step,
+//              erfcx from a table of short polynomials in LDS.  Used when the
+//              storage dtype is binary32, where a binary32 exponent argument alone
+//              would cost 5-70 ulp in the left tail.
 // The backward approximation q (Eqs. (5)-(8)) is evaluated in binary32 for both
 // dtypes; for binary32 storage its product with the gradient is rounded once.
 //
@@ -82,14 +82,17 @@ __device__ __forceinline__ float act_fast(float x)
         constexpr float k2 = (float)(kSqrt2OverPi * kLog2eD * kGeluCubic);
         u = x_gate_fast(x, -fabsf(x * fmaf(k2, x * x, k1)));
     } else {
-        // Phi(-|x|) = erfc(z) / 2 = erfcx(z) exp(-z^2) / 2 with z = |x| / sqrt 2
+        // Phi(-|x|) = erfc(z) / 2 = erfcx(z) exp(-z^2) / 2 with z = |x| / sqrt 2; the result is
+        // max(x, -0) - |x| Phi(-|x|) as one fused multiply-add.  |x| is clamped so that an infinite x meets
+        // Phi = 0 as a finite factor; a NaN x arrives through w.
         constexpr float pz = (float)(cst::erfcx_fast_p * kInvSqrt2);
+        constexpr int deg = sizeof(cst::erfcx_fast) / sizeof(cst::erfcx_fast[0]) - 1;
         float w = hw_rcp(fmaf(pz, fabsf(x), 1.0f));
-        float g = 0.5f * cst::erfcx_fast[4];
+        float g = 0.5f * cst::erfcx_fast[deg];
 #pragma unroll
-        for (int k = 3; k >= 0; --k) g = fmaf(g, w, 0.5f * cst::erfcx_fast[k]);
+        for (int k = deg - 1; k >= 0; --k) g = fmaf(g, w, 0.5f * cst::erfcx_fast[k]);
         float E = hw_exp2((x * x) * (-0.5f * kLog2e));            // exp(-z^2)
-        u = (med3(x, -FLT_MAX, FLT_MAX) * (g * w)) * E;
+        return fmaf(-med3(fabsf(x), 0.0f, FLT_MAX), (g * w) * E, med3(x, -0.0f, fabsf(x)));
     }
     // max(x, -0) as the median of (x, -0, |x|): one instruction (a median against the constant +inf is
     // rewritten by the compiler into a maximum preceded by a canonicalising v_max x, x).  A NaN x comes through u.
@@ -99,6 +102,36 @@ __device__ __forceinline__ float act_fast(float x)
 // ---------------------------------------------------------------------------
 // Forward, PRECISE
 // ---------------------------------------------------------------------------
+
+// erfcx by table, for the erf form with binary32 storage.  G(x) = Phi(-x) exp(x^2 / 2) = erfcx(x / sqrt 2) / 2 is
+// smooth and slowly varying, so on [0, 14.5) -- beyond, x Phi(-x) is below half the smallest binary32 subnormal --
+// 116 intervals of width 1/8 with a degree-4 polynomial each reach 3e-9.  The interval index and the position
+// inside it come from 8 |x| with one conversion and one v_fract_f32, both exact, and the five coefficients from
+// LDS: 10 slow-rate instructions less per element than the reciprocal-based fit (1 / (1 + p z) to 2^-30 needs a
+// Newton step in binary64, and its polynomial twice the degree).  Rows are 40 bytes apart, i.e. 10 banks: the
+// lanes of a wavefront read 16 neighbouring rows without a bank conflict.  Every wavefront copies the table
+// from global memory (4640 bytes, L2-resident) into its workgroup's LDS before its first element.
+__device__ const double g_mills_table[cst::mills_rows * cst::mills_cols] = { INVACT_MILLS_TABLE };
+constexpr int kMillsTableBytes = cst::mills_rows * cst::mills_cols * 8;
+constexpr float kMillsClamp = 14.49f;                      // 8 * 14.49 < mills_rows
+
+__device__ __forceinline__ double* mills_lds()
+{
+    __shared__ __attribute__((aligned(16))) double table[cst::mills_rows * cst::mills_cols];
+    return table;
+}
+
+// One wavefront (the whole workgroup) fills the LDS copy; `lane` = threadIdx.x < 64.
+__device__ __forceinline__ void fill_mills_table(unsigned lane)
+{
+    typedef double double2_t __attribute__((ext_vector_type(2)));
+    static_assert(cst::mills_rows * cst::mills_cols % 2 == 0, "copied in 16-byte pieces");
+    constexpr unsigned pieces = cst::mills_rows * cst::mills_cols / 2;
+    const double2_t* src = reinterpret_cast<const double2_t*>(g_mills_table);
+    double2_t* dst = reinterpret_cast<double2_t*>(mills_lds());
+    for (unsigned k = lane; k < pieces; k += 64) dst[k] = src[k];
+    __syncthreads();
+}
 
 // 2^(a b) for a binary64 product t = a b in [-30000, 0]:  t = n + f with n = round(t), |f| <= 1/2,
 // 2^f by a degree-6 polynomial in binary64 (relative error 2.6e-9: the hardware exponential's
@@ -125,36 +158,49 @@ __device__ __forceinline__ double rcp_newton(double d)
     return r * fma(-d, r, 2.0);
 }
 
-// f(x) in binary64.  For SiLU and the tanh form the clamp of x drops a NaN and the callers put it
-// back (nan_through); in the erf form the NaN arrives through w.
+// The gate on the negative side in binary64: P = sigmoid(-|z|) or Phi(-|x|), and the clamped x it was computed
+// from (|x| is clamped where P is exactly 0 anyway, so that an infinite x meets that 0 as a finite factor).
+// The clamp drops a NaN and the callers put it back (nan_through).
+struct Gate { double P; float xc; };
+
+template <int KIND>
+__device__ __forceinline__ Gate gate_precise(float x)
+{
+    Gate out;
+    if constexpr (KIND == SILU) {
+        out.xc = med3(x, -2048.0f, 2048.0f);                   // beyond, the gate underflows to 0 anyway
+        double E  = exp2_neg(-fabs((double)out.xc), kLog2eD);
+        out.P = E * rcp_newton(1.0 + E);
+    } else if constexpr (KIND == GELU_TANH) {
+        constexpr double a = 2.0 * kSqrt2OverPi * kLog2eD, b = a * kGeluCubic;
+        out.xc = med3(x, -64.0f, 64.0f);
+        double xd = (double)out.xc;
+        double E  = exp2_neg(-fabs(xd), fma(b, xd * xd, a));     // a, b > 0
+        out.P = E * rcp_newton(1.0 + E);
+    } else {
+        // G from the table (see above), times exp(-x^2 / 2).  Beyond the clamp x Phi(-x) rounds to -0 or leaves x
+        // as it is, with the clamped P as with the true one.
+        static_assert(kMillsClamp * cst::mills_per_unit < cst::mills_rows, "the clamp keeps the row index inside the table");
+        out.xc = med3(x, -kMillsClamp, kMillsClamp);
+        double xd = (double)out.xc;
+        float m = fabsf(out.xc) * (float)cst::mills_per_unit;
+        const double* row = mills_lds() + __umul24((unsigned)m, cst::mills_cols);   // truncation: the interval
+        double t = (double)__builtin_amdgcn_fractf(m);                           // position inside it, exact
+        double g = row[cst::mills_cols - 1];
+#pragma unroll
+        for (int k = cst::mills_cols - 2; k >= 0; --k) g = fma(g, t, row[k]);
+        out.P = g * exp2_neg(xd * (-0.5 * kLog2eD), xd);
+    }
+    return out;
+}
+
+// f(x) = max(x, -0) - |x| P in binary64, one fused multiply-add: what the gated product and the sign-bit
+// variant start from.
 template <int KIND>
 __device__ __forceinline__ double act_precise(float x)
 {
-    double u;
-    if constexpr (KIND == SILU) {
-        double xd = (double)med3(x, -2048.0f, 2048.0f);        // beyond, the gate underflows to 0 anyway
-        double E  = exp2_neg(-fabs(xd), kLog2eD);
-        u = xd * E * rcp_newton(1.0 + E);
-    } else if constexpr (KIND == GELU_TANH) {
-        constexpr double a = 2.0 * kSqrt2OverPi * kLog2eD, b = a * kGeluCubic;
-        double xd = (double)med3(x, -64.0f, 64.0f);
-        double E  = exp2_neg(-fabs(xd), fma(b, xd * xd, a));     // a, b > 0
-        u = xd * E * rcp_newton(1.0 + E);
-    } else {
-        // w = 1 / (1 + p z): binary32 seed from the UNCLAMPED x (a NaN x thus reaches the result through w,
-        // and an infinite one gives w = 0), one Newton step in binary64 against the clamped argument.
-        // Beyond the clamp the two disagree, but there exp(-z^2) is exactly 0.
-        constexpr double pz = cst::erfcx_precise_p * kInvSqrt2;
-        double xd = (double)med3(x, -64.0f, 64.0f);
-        double r  = (double)hw_rcp(fmaf((float)pz, fabsf(x), 1.0f));
-        double w  = r * fma(-fma(pz, fabs(xd), 1.0), r, 2.0);
-        double g  = 0.5 * cst::erfcx_precise[9];
-#pragma unroll
-        for (int k = 8; k >= 0; --k) g = fma(g, w, 0.5 * cst::erfcx_precise[k]);
-        double E = exp2_neg(xd * (-0.5 * kLog2eD), xd);
-        u = xd * (g * w) * E;
-    }
-    return fmax((double)x, -0.0) - fabs(u);
+    Gate g = gate_precise<KIND>(x);
+    return fma(-fabs((double)g.xc), g.P, fmax((double)x, -0.0));
 }
 
 // The clamps above drop a NaN; put it back, as a quiet one: the precision-bit variant clears bit 0 of
@@ -166,7 +212,6 @@ template <int KIND, int PREC>
 __device__ __forceinline__ float act(float x)
 {
     if constexpr (PREC == FAST) return act_fast<KIND>(x);
-    else if constexpr (KIND == GELU_ERF) return (float)act_precise<KIND>(x);
     else return nan_through(x, (float)act_precise<KIND>(x));
 }
 
@@ -182,7 +227,7 @@ __device__ __forceinline__ void act_times(float gate, float up, float& a, float&
         double ad = act_precise<KIND>(gate);
         a = (float)ad;
         h = (float)(ad * (double)up);
-        if constexpr (KIND != GELU_ERF) { a = nan_through(gate, a); h = nan_through(gate, h); }
+        a = nan_through(gate, a); h = nan_through(gate, h);
     }
 }
 
@@ -200,7 +245,7 @@ __device__ __forceinline__ float act_minus_min_signed(float x)
     } else {
         double d = act_precise<KIND>(x) - (double)C;
         v = (float)((d < 0.0) ? 0.0 : d);               // keeps a NaN
-        if constexpr (KIND != GELU_ERF) v = nan_through(x, v);
+        v = nan_through(x, v);
     }
     return (x < KindConst<KIND>::T) ? -v : v;
 }

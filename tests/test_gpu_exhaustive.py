@@ -1,0 +1,104 @@
+"""Binary32 kernels against the oracle over the whole input space.
+
+Every STRIDE-th binary32 bit pattern goes through invact_fwd (all patterns) and invact_bwd (every stored y
+the backward can meet: y >= f(T) - 2^-12 with s = 0, and y in [f(T) - 2^-12, +0] with s = 1, grad_y = 1), with
+the tolerances of tests/parity.py; the forward's masks must be bit-exact.  STRIDE is 61 by default (7 * 10^7
+patterns per case, a few seconds); with INVACT_EXHAUSTIVE=1 in the environment it is 1, i.e. all 2^32 patterns
+(2-4 minutes per case):
+
+    INVACT_EXHAUSTIVE=1 python -m pytest tests/test_gpu_exhaustive.py -m gpu -s
+
+Each case prints one RESULT line (worst error in units of the tolerance, worst literal error in ulps, where).
+"""
+import os
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+import parity as PT
+from paper_2407_15545_amd import binding as B
+
+pytestmark = pytest.mark.gpu
+KINDS = ["gelu_tanh", "gelu_erf", "silu"]
+STRIDE = 1 if os.environ.get("INVACT_EXHAUSTIVE") == "1" else 61
+BLOCK = 1 << 26          # patterns per launch
+
+
+def pattern_blocks(first, last):
+    """Strided pattern ranges covering first..last inclusive, as (start, count) with stride STRIDE."""
+    a = first
+    while a <= last:
+        count = min(BLOCK, (last - a) // STRIDE + 1)
+        yield a, count
+        a += count * STRIDE
+
+
+def patterns_to_device(start, count):
+    bits = start + STRIDE * torch.arange(count, dtype=torch.int64, device="cuda")
+    return bits.to(torch.int32).view(torch.float32)       # the conversion wraps patterns >= 2^31 as intended
+
+
+class Worst:
+    def __init__(self):
+        self.tol, self.ulp, self.where_tol, self.where_ulp, self.total = 0.0, 0.0, None, None, 0
+
+    def update(self, start, got, ref, err):
+        i = int(np.nanargmax(err))
+        if err[i] > self.tol:
+            self.tol, self.where_tol = float(err[i]), (hex(start + STRIDE * i), float(got[i]), float(ref[i]))
+        with np.errstate(invalid="ignore", over="ignore"):
+            lit = np.where(np.isfinite(ref) & np.isfinite(got) & (np.abs(ref) >= 2.0 ** -126),
+                           np.abs(got - ref) / PT.ulp(ref, "fp32"), 0.0)
+        j = int(np.argmax(lit))
+        if lit[j] > self.ulp:
+            self.ulp, self.where_ulp = float(lit[j]), (hex(start + STRIDE * j), float(got[j]), float(ref[j]))
+        self.total += err.size
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_forward_over_all_binary32_inputs(kind):
+    w, mask_ok, t0 = Worst(), True, time.time()
+    for start, count in pattern_blocks(0x00000000, 0xFFFFFFFF):
+        PT.say(f"exhaustive fwd {kind}: patterns from {start:#010x}, {count} of them, stride {STRIDE}")
+        x = patterns_to_device(start, count)
+        y, m = B.invact_fwd(kind, x)
+        torch.cuda.synchronize()
+        x64 = x.cpu().numpy().astype(np.float64)
+        ye, _, m_ref = O.invact_fwd(kind, "fp32", x64)
+        mask_ok &= bool(np.array_equal(m.cpu().numpy(), m_ref))
+        got = y.cpu().numpy().astype(np.float64)
+        w.update(start, got, ye, PT.forward_errors(got, ye, "fp32"))
+    print(f"\nRESULT fwd {kind} stride {STRIDE}: {w.total} inputs, worst {w.tol:.4f} of the tolerance at {w.where_tol}, "
+          f"worst literal {w.ulp:.4g} ulp at {w.where_ulp}, masks {'bit-exact' if mask_ok else 'DIFFER'} "
+          f"[{time.time() - t0:.0f} s]", flush=True)
+    assert mask_ok
+    assert w.tol <= 1.0, w.where_tol
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_backward_over_all_binary32_saved_outputs(kind):
+    fT = np.float32(O.fT(kind, f32=True))
+    lo = np.float32(fT - np.float32(2.0 ** -12))
+    lo_bits = int(np.array([lo]).view(np.uint32)[0])          # negative: larger pattern = more negative
+    ranges = [(0x00000000, 0x7F800000, 0),                     # s = 0: +0 .. +inf
+              (0x80000000, lo_bits, 0),                        # s = 0: -0 .. f(T) - 2^-12
+              (0x80000000, lo_bits, 1),                        # s = 1: -0 .. f(T) - 2^-12
+              (0x00000000, 0x00000000, 1)]                     # s = 1: +0
+    w, t0 = Worst(), time.time()
+    for first, last, s in ranges:
+        for start, count in pattern_blocks(first, last):
+            PT.say(f"exhaustive bwd {kind} s={s}: patterns from {start:#010x}, {count} of them, stride {STRIDE}")
+            y = patterns_to_device(start, count)
+            mask = torch.full((B.mask_bytes(count),), 0xFF if s else 0, dtype=torch.uint8, device="cuda")
+            gx = B.invact_bwd(kind, y, mask, torch.ones(count, dtype=torch.float32, device="cuda"))
+            torch.cuda.synchronize()
+            y64 = y.cpu().numpy().astype(np.float64)
+            ref = O.q(kind, y64, np.full(count, s, np.uint8))
+            got = gx.cpu().numpy().astype(np.float64)
+            w.update(start, got, ref, PT.backward_errors(got, ref, np.ones(count), "fp32"))
+    print(f"\nRESULT bwd {kind} stride {STRIDE}: {w.total} cases, worst {w.tol:.4f} of the tolerance at {w.where_tol}, "
+          f"worst literal {w.ulp:.4g} ulp at {w.where_ulp} [{time.time() - t0:.0f} s]", flush=True)
+    assert w.tol <= 1.0, w.where_tol
