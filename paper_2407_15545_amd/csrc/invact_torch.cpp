@@ -6,6 +6,8 @@
 // Python autograd.Function hops cost.  No arithmetic happens here.
 //
 // Built by build.py into libinvact_torch.so (host code only; links libinvact.so and libtorch).
+#include <cstdint>
+
 #include <ATen/ATen.h>
 #include <c10/core/DeviceGuard.h>
 #include <c10/hip/HIPStream.h>
@@ -34,6 +36,14 @@ int dtype_of(const at::Tensor& t)
 
 hipStream_t stream_of(const at::Tensor& t) { return c10::hip::getCurrentHIPStream(t.device().index()).stream(); }
 
+// t as the library wants it: contiguous, and starting on a 16-byte boundary.  A contiguous view into the middle
+// of another tensor (t.view(-1)[3:]) is contiguous but need not be aligned: it is copied.
+at::Tensor dense(const at::Tensor& t)
+{
+    at::Tensor c = t.contiguous();
+    return reinterpret_cast<uintptr_t>(c.data_ptr()) % 16 == 0 ? c : c.clone();
+}
+
 at::Tensor new_mask(const at::Tensor& like)
 {
     return at::empty({(int64_t)invact_mask_bytes((size_t)like.numel())}, like.options().dtype(at::kByte));
@@ -43,7 +53,7 @@ struct Act : torch::autograd::Function<Act> {
     static at::Tensor forward(AutogradContext* ctx, const at::Tensor& x, int64_t kind)
     {
         const int dt = dtype_of(x);
-        const at::Tensor xc = x.contiguous();
+        const at::Tensor xc = dense(x);
         at::Tensor y = at::empty_like(xc), mask = new_mask(xc);
         const c10::DeviceGuard guard(xc.device());
         check(invact_fwd((int)kind, dt, xc.data_ptr(), y.data_ptr(), mask.data_ptr(), (size_t)xc.numel(), stream_of(xc)));
@@ -55,7 +65,7 @@ struct Act : torch::autograd::Function<Act> {
     {
         const auto saved = ctx->get_saved_variables();
         const at::Tensor &y = saved[0], &mask = saved[1];
-        const at::Tensor g = grads[0].contiguous();
+        const at::Tensor g = dense(grads[0]);
         at::Tensor gx = at::empty_like(g);
         const c10::DeviceGuard guard(g.device());
         check(invact_bwd((int)ctx->saved_data["kind"].toInt(), dtype_of(g), y.data_ptr(), mask.data_ptr(), g.data_ptr(),
@@ -68,7 +78,7 @@ struct ActPbit : torch::autograd::Function<ActPbit> {
     static at::Tensor forward(AutogradContext* ctx, const at::Tensor& x, int64_t kind)
     {
         const int dt = dtype_of(x);
-        const at::Tensor xc = x.contiguous();
+        const at::Tensor xc = dense(x);
         at::Tensor y = at::empty_like(xc);
         const c10::DeviceGuard guard(xc.device());
         check(invact_pbit_fwd((int)kind, dt, xc.data_ptr(), y.data_ptr(), (size_t)xc.numel(), stream_of(xc)));
@@ -79,7 +89,7 @@ struct ActPbit : torch::autograd::Function<ActPbit> {
     static variable_list backward(AutogradContext* ctx, variable_list grads)
     {
         const at::Tensor y = ctx->get_saved_variables()[0];
-        const at::Tensor g = grads[0].contiguous();
+        const at::Tensor g = dense(grads[0]);
         at::Tensor gx = at::empty_like(g);
         const c10::DeviceGuard guard(g.device());
         check(invact_pbit_bwd((int)ctx->saved_data["kind"].toInt(), dtype_of(g), y.data_ptr(), g.data_ptr(), gx.data_ptr(),
@@ -94,7 +104,7 @@ struct Glu : torch::autograd::Function<Glu> {
         TORCH_CHECK(gate.sizes() == up.sizes() && gate.scalar_type() == up.scalar_type() && gate.device() == up.device(),
                     "gate and up must share shape, dtype and device");
         const int dt = dtype_of(gate);
-        const at::Tensor gc = gate.contiguous(), uc = up.contiguous();
+        const at::Tensor gc = dense(gate), uc = dense(up);
         at::Tensor act = at::empty_like(gc), h = at::empty_like(gc), mask = new_mask(gc);
         const c10::DeviceGuard guard(gc.device());
         check(geglu_invact_fwd((int)kind, dt, gc.data_ptr(), uc.data_ptr(), act.data_ptr(), h.data_ptr(),
@@ -107,7 +117,7 @@ struct Glu : torch::autograd::Function<Glu> {
     {
         const auto saved = ctx->get_saved_variables();
         const at::Tensor &act = saved[0], &up = saved[1], &mask = saved[2];
-        const at::Tensor g = grads[0].contiguous();
+        const at::Tensor g = dense(grads[0]);
         at::Tensor gg = at::empty_like(g), gu = at::empty_like(g);
         const c10::DeviceGuard guard(g.device());
         check(geglu_invact_bwd((int)ctx->saved_data["kind"].toInt(), dtype_of(g), act.data_ptr(), up.data_ptr(),

@@ -55,10 +55,17 @@ def set_wiring(name):
     return previous
 
 
+def _dense(t):
+    """t as the library wants it: contiguous, and starting on a 16-byte boundary.  A contiguous view into the
+    middle of another tensor (t.view(-1)[3:]) is contiguous but need not be aligned: it is copied."""
+    t = t.contiguous()
+    return t if t.data_ptr() % 16 == 0 else t.clone()
+
+
 class _InvAct(torch.autograd.Function):
     @staticmethod
     def forward(ctx, x, kind):
-        y, mask = B.invact_fwd(kind, x.contiguous())
+        y, mask = B.invact_fwd(kind, _dense(x))
         ctx.kind = kind
         ctx.save_for_backward(y, mask)
         return y.view_as(x)
@@ -66,13 +73,13 @@ class _InvAct(torch.autograd.Function):
     @staticmethod
     def backward(ctx, grad_y):
         y, mask = ctx.saved_tensors
-        return B.invact_bwd(ctx.kind, y, mask, grad_y.contiguous()).view_as(grad_y), None
+        return B.invact_bwd(ctx.kind, y, mask, _dense(grad_y)).view_as(grad_y), None
 
 
 class _InvActPrecisionBit(torch.autograd.Function):
     @staticmethod
     def forward(ctx, x, kind):
-        y = B.invact_pbit_fwd(kind, x.contiguous())
+        y = B.invact_pbit_fwd(kind, _dense(x))
         ctx.kind = kind
         ctx.save_for_backward(y)
         return y.view_as(x)
@@ -80,14 +87,14 @@ class _InvActPrecisionBit(torch.autograd.Function):
     @staticmethod
     def backward(ctx, grad_y):
         (y,) = ctx.saved_tensors
-        return B.invact_pbit_bwd(ctx.kind, y, grad_y.contiguous()).view_as(grad_y), None
+        return B.invact_pbit_bwd(ctx.kind, y, _dense(grad_y)).view_as(grad_y), None
 
 
 class _InvActGLU(torch.autograd.Function):
     @staticmethod
     def forward(ctx, gate, up, kind):
-        up = up.contiguous()
-        act, h, mask = B.geglu_invact_fwd(kind, gate.contiguous(), up)
+        up = _dense(up)
+        act, h, mask = B.geglu_invact_fwd(kind, _dense(gate), up)
         ctx.kind = kind
         ctx.save_for_backward(act, up, mask)
         return h.view_as(gate)
@@ -95,7 +102,7 @@ class _InvActGLU(torch.autograd.Function):
     @staticmethod
     def backward(ctx, grad_h):
         act, up, mask = ctx.saved_tensors
-        grad_gate, grad_up = B.geglu_invact_bwd(ctx.kind, act, up, mask, grad_h.contiguous())
+        grad_gate, grad_up = B.geglu_invact_bwd(ctx.kind, act, up, mask, _dense(grad_h))
         return grad_gate.view_as(grad_h), grad_up.view_as(grad_h), None
 
 
@@ -106,7 +113,7 @@ class _SignBitActLinear(torch.autograd.Function):
 
     @staticmethod
     def forward(ctx, x, weight, bias, kind):
-        y_tagged = B.invact_sbit_fwd(kind, x.contiguous())
+        y_tagged = B.invact_sbit_fwd(kind, _dense(x))
         out = torch.nn.functional.linear(B.invact_sbit_decode(kind, y_tagged).view_as(x), weight, bias)
         ctx.kind, ctx.has_bias = kind, bias is not None
         ctx.save_for_backward(y_tagged, weight)
@@ -119,7 +126,7 @@ class _SignBitActLinear(torch.autograd.Function):
         y2 = B.invact_sbit_decode(ctx.kind, y_tagged).view(-1, weight.shape[1])
         grad_w = g2.t().mm(y2)
         grad_b = g2.sum(0) if ctx.has_bias else None
-        grad_y = g2.mm(weight).contiguous()
+        grad_y = _dense(g2.mm(weight))
         grad_x = B.invact_sbit_bwd(ctx.kind, y_tagged.view(-1), grad_y.view(-1)).view(y_tagged.shape)
         return grad_x, grad_w, grad_b, None
 

@@ -26,13 +26,15 @@ BF16_MAX = float.fromhex("0x1.fep127")
 MAX_FINITE = {"fp32": F32_MAX, "bf16": BF16_MAX}
 
 
-REPORT_DIR = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+# INVACT_REPORT_DIR: where a run may leave its reports (the names of the cases it ran, accuracy figures);
+# nothing is written when it is not set.
+REPORT_DIR = os.environ.get("INVACT_REPORT_DIR") or None
 
 
 def say(*a):
-    """Name the case before a GPU step (stderr, flushed) and keep a copy where GPU runs leave their files."""
+    """Name the case before a GPU step (stderr, flushed); with INVACT_REPORT_DIR set, also keep a copy there."""
     print(*a, file=sys.stderr, flush=True)
-    if os.path.isdir(REPORT_DIR):
+    if REPORT_DIR and os.path.isdir(REPORT_DIR):
         with open(os.path.join(REPORT_DIR, "parity_report.txt"), "a") as fh:
             print(*a, file=fh)
 

@@ -6,6 +6,7 @@ import torch
 import torch.nn.functional as F
 
 import parity as PT
+from paper_2407_15545_amd import binding as B
 from paper_2407_15545_amd import nn as inv
 
 pytestmark = pytest.mark.gpu
@@ -40,6 +41,77 @@ def test_layer_matches_torch_autograd(kind, dtype, precision_bit):
     assert torch.all((y.double() - yr).abs() <= eps * yr.abs() + 1e-9)
     # q approximates f'(x) to a few 1e-2 at worst (GELU just right of the minimum)
     assert torch.all((gx.double() - gr).abs() <= (4e-2 + 4 * eps) * g.double().abs() + 1e-9)
+
+
+@pytest.mark.parametrize("precision_bit", [False, True])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("kind", ["gelu_erf", "gelu_tanh", "silu"])
+def test_layer_is_the_c_abi_bit_for_bit(kind, dtype, precision_bit):
+    """The layer adds nothing to the kernels: its output, what it saves and its gradient are bit-identical to
+    direct calls of the binding on the same tensors (a wrong kind, or y and x exchanged, cannot hide here)."""
+    torch.manual_seed(4)
+    x = (torch.randn(37, 1001, device="cuda") * 2).to(dtype).requires_grad_()
+    g = torch.randn(37, 1001, device="cuda").to(dtype)
+    PT.say(f"nn layer vs binding {kind} {dtype} precision_bit={precision_bit}")
+    saved = []
+    with torch.autograd.graph.saved_tensors_hooks(lambda t: saved.append(t) or t, lambda t: t):
+        y = inv.invact(x, kind, precision_bit)
+    (gx,) = torch.autograd.grad(y, x, g)
+    same = lambda a, b: a.shape == b.shape and torch.equal(a.contiguous().view(torch.uint8), b.contiguous().view(torch.uint8))
+    flat = x.detach().reshape(-1)
+    if precision_bit:
+        y_ref = B.invact_pbit_fwd(kind, flat)
+        gx_ref = B.invact_pbit_bwd(kind, y_ref, g.reshape(-1))
+        assert len(saved) == 1 and same(saved[0].reshape(-1), y_ref)
+    else:
+        y_ref, m_ref = B.invact_fwd(kind, flat)
+        gx_ref = B.invact_bwd(kind, y_ref, m_ref, g.reshape(-1))
+        assert len(saved) == 2 and same(saved[0].reshape(-1), y_ref) and same(saved[1], m_ref)
+    assert same(y.detach(), y_ref.view_as(x)) and same(gx, gx_ref.view_as(x))
+
+
+@pytest.mark.parametrize("kind", ["silu", "gelu_erf", "gelu_tanh"])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_glu_layer_is_the_c_abi_bit_for_bit(kind, dtype):
+    torch.manual_seed(5)
+    gate = torch.randn(33, 515, device="cuda").to(dtype).requires_grad_()
+    up = torch.randn(33, 515, device="cuda").to(dtype).requires_grad_()
+    gh = torch.randn(33, 515, device="cuda").to(dtype)
+    PT.say(f"nn glu vs binding {kind} {dtype}")
+    saved = []
+    with torch.autograd.graph.saved_tensors_hooks(lambda t: saved.append(t) or t, lambda t: t):
+        h = inv.invact_glu(gate, up, kind)
+    gg, gu = torch.autograd.grad(h, (gate, up), gh)
+    same = lambda a, b: torch.equal(a.contiguous().view(torch.uint8).reshape(-1), b.contiguous().view(torch.uint8).reshape(-1))
+    act_ref, h_ref, m_ref = B.geglu_invact_fwd(kind, gate.detach().reshape(-1), up.detach().reshape(-1))
+    gg_ref, gu_ref = B.geglu_invact_bwd(kind, act_ref, up.detach().reshape(-1), m_ref, gh.reshape(-1))
+    assert len(saved) == 3 and same(saved[0], act_ref) and same(saved[1], up.detach()) and same(saved[2], m_ref)
+    assert same(h.detach(), h_ref) and same(gg, gg_ref) and same(gu, gu_ref)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_layers_take_misaligned_contiguous_views(dtype):
+    """t.view(-1)[3:] is contiguous but starts 6 or 12 bytes into an allocation: the library wants 16-byte
+    alignment, so the layers copy such an input (and such an incoming gradient) instead of raising."""
+    torch.manual_seed(6)
+    n = 5000
+    base = (torch.randn(n + 3, device="cuda") * 2).to(dtype)
+    gbase = torch.randn(n + 3, device="cuda").to(dtype)
+    x = base[3:].detach().requires_grad_()
+    g = gbase[3:]
+    assert x.is_contiguous() and x.data_ptr() % 16 != 0 and g.data_ptr() % 16 != 0
+    PT.say(f"nn layers on misaligned views {dtype}")
+    aligned_x = base[3:].clone().requires_grad_()
+    for fn in (lambda t: inv.invact(t, "gelu_erf"), lambda t: inv.invact(t, "silu", True),
+               lambda t: inv.invact_glu(t, t.detach() * 0.5, "silu")):
+        y = fn(x)
+        (gx,) = torch.autograd.grad(y, x, g)
+        y2 = fn(aligned_x)
+        (gx2,) = torch.autograd.grad(y2, aligned_x, g.clone())
+        assert torch.equal(y.detach().view(torch.uint8), y2.detach().view(torch.uint8))
+        assert torch.equal(gx.view(torch.uint8), gx2.view(torch.uint8))
+    with pytest.raises(B.InvactError):                      # the C ABI itself still refuses the pointer
+        B.invact_fwd("silu", x.detach())
 
 
 @pytest.mark.parametrize("kind", ["silu", "gelu_erf"])

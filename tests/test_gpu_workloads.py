@@ -1,12 +1,15 @@
 """GPU parity at the full sizes of the five benchmark workloads, in the launch
 configuration bench.py times (the library's default).
 
-Per workload: the branch mask is compared bit for bit over the whole tensor;
-floating-point outputs are compared on a sample the oracle evaluates one by
-one (both ends of the tensor plus 2^20 random positions); the backward runs on
-what the ORACLE's forward saved.  The approximation error of q against the
-exact derivative (which the paper only plots) is written to
-accuracy_report.json in the folder GPU runs leave their files in.
+For the four transformer-shaped workloads EVERY element is compared with the
+oracle (masks bit for bit, floating-point outputs within the tolerances of
+parity.py), block by block; the backward runs on what the ORACLE's forward
+saved.  The 2^28-element stress workloads compare the whole mask and the floats
+on both ends of the tensor plus 2^20 random positions (their dense blocks
+around the minimum sit at the front).  The approximation error of q against the
+exact derivative (which the paper only plots) and the literal result-relative
+error of the backward are reported, not asserted: printed, and written to
+accuracy_report.json when INVACT_REPORT_DIR names a folder.
 """
 import json
 import os
@@ -21,14 +24,14 @@ from paper_2407_15545_amd import binding as B
 import synth
 
 pytestmark = pytest.mark.gpu
-REPORT_DIR = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
 CHUNK = 1 << 25          # oracle block (a multiple of 64, so mask words do not straddle blocks)
 
 
 def report(key, value):
-    if not os.path.isdir(REPORT_DIR):
+    print(f"ACCURACY {key} {json.dumps(value, sort_keys=True)}", flush=True)
+    if not (PT.REPORT_DIR and os.path.isdir(PT.REPORT_DIR)):
         return
-    path = os.path.join(REPORT_DIR, "accuracy_report.json")
+    path = os.path.join(PT.REPORT_DIR, "accuracy_report.json")
     data = json.load(open(path)) if os.path.exists(path) else {}
     data[key] = value
     json.dump(data, open(path, "w"), indent=1, sort_keys=True)
@@ -41,13 +44,16 @@ def sample_positions(n, seed=7, k=1 << 20):
     return np.unique(idx)
 
 
+def blocks(n):
+    return [(o, min(CHUNK, n - o)) for o in range(0, n, CHUNK)]
+
+
 def oracle_forward_full(kind, dtype, x_storage):
     """Oracle forward over the whole tensor in blocks -> (stored y as a storage array, mask)."""
     n = x_storage.size
     ys = np.empty(n, dtype=np.float32 if dtype == "fp32" else np.uint16)
     mask = np.zeros(O.mask_bytes(n), dtype=np.uint8)
-    for o in range(0, n, CHUNK):
-        m = min(CHUNK, n - o)
+    for o, m in blocks(n):
         _, y_st, mk = O.invact_fwd(kind, dtype, synth.storage_to_f64(x_storage[o:o + m], dtype))
         ys[o:o + m] = synth.f64_to_storage_exact(y_st, dtype)
         mask[o // 8:o // 8 + mk.size] = mk
@@ -60,7 +66,41 @@ def error_stats(q, exact):
     return {"max_abs": float(np.max(np.abs(d[ok]))), "rel_l2": float(np.sqrt(np.sum(d[ok] ** 2) / np.sum(exact[ok] ** 2)))}
 
 
-def run_plain(name, kind, dtype, w):
+class Literal:
+    """Result-relative error of a backward output over a whole tensor: maximum in ulps of the storage dtype and
+    the share of elements more than 2 ulp away (the figure the two-armed tolerance of parity.py does not show)."""
+    def __init__(self):
+        self.max_ulp, self.over, self.count = 0.0, 0, 0
+
+    def add(self, got, ref, dtype):
+        ok = np.isfinite(ref) & np.isfinite(got) & (np.abs(ref) >= 2.0 ** -126)
+        lit = PT.literal_ulps(got[ok], ref[ok], dtype)
+        if lit.size:
+            self.max_ulp = max(self.max_ulp, float(lit.max()))
+            self.over += int((lit > 2.0).sum())
+            self.count += int(lit.size)
+
+    def summary(self):
+        return {"max_ulp": self.max_ulp, "share_over_2_ulp": self.over / max(self.count, 1)}
+
+
+def check_all(name, what, gpu_tensor, dtype, reference, scale=None):
+    """Every element of gpu_tensor against reference(o, m) -> float64 block (and scale(o, m) for the backward
+    tolerance); returns the largest error in units of the tolerance and the literal statistics."""
+    n = gpu_tensor.numel()
+    worst, lit = 0.0, Literal()
+    for o, m in blocks(n):
+        got = PT.to_f64(gpu_tensor[o:o + m])
+        ref = reference(o, m)
+        e = PT.forward_errors(got, ref, dtype) if scale is None else PT.backward_errors(got, ref, scale(o, m), dtype)
+        i = int(np.argmax(e))
+        assert e[i] <= 1.0, f"{name} {what}: element {o + i}: got {got[i]!r}, oracle {ref[i]!r}, {e[i]:.3f} of the tolerance"
+        worst = max(worst, float(e[i]))
+        lit.add(got, ref, dtype)
+    return worst, lit.summary()
+
+
+def run_plain(name, kind, dtype, w, every_element):
     n = w["n"]
     x_st, g_st = w["x"], w["grad_y"]
     idx = sample_positions(n)
@@ -73,66 +113,81 @@ def run_plain(name, kind, dtype, w):
     torch.cuda.synchronize()
     assert np.array_equal(m.cpu().numpy(), m_ref), "mask differs"
     x64 = synth.storage_to_f64(x_st[idx], dtype)
-    ye = O.f(kind, x64)
-    e = PT.forward_errors(PT.to_f64(y[it]), ye, dtype)
-    assert e.max() <= 1.0, PT.worst(e, x64, ye, PT.to_f64(y[it]))
+    stats = {"n": n, "floats_compared": n if every_element else int(idx.size)}
+    if every_element:
+        stats["fwd_max_tolerance_units"], _ = check_all(
+            name, "y", y, dtype, lambda o, k: O.f(kind, synth.storage_to_f64(x_st[o:o + k], dtype)))
+    else:
+        ye = O.f(kind, x64)
+        e = PT.forward_errors(PT.to_f64(y[it]), ye, dtype)
+        assert e.max() <= 1.0, PT.worst(e, x64, ye, PT.to_f64(y[it]))
+        stats["fwd_max_tolerance_units"] = float(e.max())
     del y
 
     PT.say(f"{name}: invact_bwd")
     gx = B.invact_bwd(kind, PT.to_device(ys_st, dtype), torch.from_numpy(m_ref).cuda(), PT.to_device(g_st, dtype))
     torch.cuda.synchronize()
+    s_all = O.unpack(m_ref, n)
     ys64 = synth.storage_to_f64(ys_st[idx], dtype)
     g64 = synth.storage_to_f64(g_st[idx], dtype)
-    s = O.unpack(m_ref, n)[idx]
+    s = s_all[idx]
     q = O.q(kind, ys64, s)
     got = PT.to_f64(gx[it])
-    e = PT.backward_errors(got, g64 * q, g64, dtype)
-    assert e.max() <= 1.0, PT.worst(e, ys64, g64, g64 * q, got)
+    if every_element:
+        def ref_block(o, k):
+            return O.invact_bwd(kind, synth.storage_to_f64(ys_st[o:o + k], dtype), m_ref[o // 8:(o + k + 7) // 8],
+                                synth.storage_to_f64(g_st[o:o + k], dtype))
+        stats["bwd_max_tolerance_units"], stats["bwd_literal"] = check_all(
+            name, "grad_x", gx, dtype, ref_block, lambda o, k: synth.storage_to_f64(g_st[o:o + k], dtype))
+    else:
+        e = PT.backward_errors(got, g64 * q, g64, dtype)
+        assert e.max() <= 1.0, PT.worst(e, ys64, g64, g64 * q, got)
+        lit = Literal(); lit.add(got, g64 * q, dtype)
+        stats["bwd_max_tolerance_units"], stats["bwd_literal"] = float(e.max()), lit.summary()
 
-    # accuracy of the approximation itself (reported, the paper states no bound)
+    # accuracy of the approximation itself on the sample (reported, the paper states no bound)
     exact_x = O.df(kind, x64)
     with np.errstate(invalid="ignore"):
         exact_y = O.df(kind, O.finv(kind, ys64, s))
     nz = g64 != 0
     q_gpu = np.where(nz, got / np.where(nz, g64, 1.0), np.nan)
-    report(f"{name}/{kind}/{dtype}", {
-        "n": n, "sample": int(idx.size),
+    stats.update({
+        "sample": int(idx.size),
         "q_vs_exact_derivative_at_stored_y": error_stats(q, exact_y),
         "q_vs_exact_derivative_at_x (end to end)": error_stats(q, exact_x),
         "gpu_q_vs_exact_derivative_at_x (end to end)": error_stats(q_gpu, exact_x),
-        "gpu_vs_oracle_max_tolerance_units": float(e.max()),
         "left_branch_share": float(s.mean()),
     })
+    report(f"{name}/{kind}/{dtype}", stats)
 
 
 def test_workload_gelu_tanh_fp32():
     name = "gelu_tanh_fp32_4x128x3072"
-    run_plain(name, "gelu_tanh", "fp32", synth.make(name))
+    run_plain(name, "gelu_tanh", "fp32", synth.make(name), every_element=True)
 
 
 def test_workload_gelu_erf_bf16():
     name = "gelu_erf_bf16_32x512x3072"
-    run_plain(name, "gelu_erf", "bf16", synth.make(name))
+    run_plain(name, "gelu_erf", "bf16", synth.make(name), every_element=True)
 
 
 def test_workload_silu_bf16():
     name = "silu_bf16_8x2048x11008"
-    run_plain(name, "silu", "bf16", synth.make(name))
+    run_plain(name, "silu", "bf16", synth.make(name), every_element=True)
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "fp32"])
 @pytest.mark.parametrize("kind", ["gelu_tanh", "gelu_erf", "silu"])
 def test_workload_stress_2p28(kind, dtype):
     w = synth.make("stress_2p28", kind=kind, dtype=dtype, T=O.T(kind, f32=True))
-    run_plain("stress_2p28", kind, dtype, w)
+    run_plain("stress_2p28", kind, dtype, w, every_element=False)
 
 
 def test_workload_swiglu_bf16_headline():
     name, kind, dtype = "swiglu_bf16_4x4096x14336", "silu", "bf16"
     w = synth.make(name)
     n = w["n"]
-    idx = sample_positions(n)
-    it = torch.from_numpy(idx).cuda()
+    f64 = lambda key, o, k: synth.storage_to_f64(w[key][o:o + k], dtype)
     PT.say(f"{name}: oracle forward n={n}")
     as_st, m_ref = oracle_forward_full(kind, dtype, w["gate"])
 
@@ -140,31 +195,30 @@ def test_workload_swiglu_bf16_headline():
     act, h, m = B.swiglu_invact_fwd(PT.to_device(w["gate"], dtype), PT.to_device(w["up"], dtype))
     torch.cuda.synchronize()
     assert np.array_equal(m.cpu().numpy(), m_ref), "mask differs"
-    gate, up, gh = (synth.storage_to_f64(w[k][idx], dtype) for k in ("gate", "up", "grad_h"))
-    ae = O.f(kind, gate)
-    e1 = PT.forward_errors(PT.to_f64(act[it]), ae, dtype)
-    e2 = PT.forward_errors(PT.to_f64(h[it]), ae * up, dtype)
-    assert e1.max() <= 1.0, PT.worst(e1, gate, ae, PT.to_f64(act[it]))
-    assert e2.max() <= 1.0, PT.worst(e2, gate, up, ae * up, PT.to_f64(h[it]))
-    # the stored activation is bit-identical to the oracle's on the whole sample
-    assert np.array_equal(act[it].view(torch.int16).cpu().numpy().view(np.uint16), as_st[idx])
+    # the stored activation is bit-identical to the oracle's over the whole tensor
+    assert np.array_equal(act.view(torch.int16).cpu().numpy().view(np.uint16), as_st)
+    stats = {"n": n, "floats_compared": n}
+    stats["h_max_tolerance_units"], _ = check_all(
+        name, "h", h, dtype, lambda o, k: O.f(kind, f64("gate", o, k)) * f64("up", o, k))
     del act, h
 
     PT.say(f"{name}: swiglu_invact_bwd")
     gg, gu = B.swiglu_invact_bwd(PT.to_device(as_st, dtype), PT.to_device(w["up"], dtype),
                                  torch.from_numpy(m_ref).cuda(), PT.to_device(w["grad_h"], dtype))
     torch.cuda.synchronize()
-    a64 = synth.storage_to_f64(as_st[idx], dtype)
-    s = O.unpack(m_ref, n)[idx]
-    gg_ref, gu_ref = O.glu_bwd(kind, a64, up, O.pack(s), gh)
-    e3 = PT.forward_errors(PT.to_f64(gu[it]), gu_ref, dtype)
-    e4 = PT.backward_errors(PT.to_f64(gg[it]), gg_ref, gh * up, dtype)
-    assert e3.max() <= 1.0, PT.worst(e3, gh, a64, gu_ref, PT.to_f64(gu[it]))
-    assert e4.max() <= 1.0, PT.worst(e4, a64, gh * up, gg_ref, PT.to_f64(gg[it]))
-    q = O.q(kind, a64, s)
-    report(f"{name}/{kind}/{dtype}", {
-        "n": n, "sample": int(idx.size),
-        "q_vs_exact_derivative_at_x (end to end)": error_stats(q, O.df(kind, gate)),
-        "gpu_vs_oracle_max_tolerance_units": float(e4.max()),
-        "left_branch_share": float(s.mean()),
+    s_all = O.unpack(m_ref, n)
+    a64 = lambda o, k: synth.storage_to_f64(as_st[o:o + k], dtype)
+    glu_bwd = lambda o, k: O.glu_bwd(kind, a64(o, k), f64("up", o, k), m_ref[o // 8:(o + k + 7) // 8], f64("grad_h", o, k))
+    stats["grad_up_max_tolerance_units"], stats["grad_up_literal"] = check_all(
+        name, "grad_up", gu, dtype, lambda o, k: glu_bwd(o, k)[1])
+    stats["grad_gate_max_tolerance_units"], stats["grad_gate_literal"] = check_all(
+        name, "grad_gate", gg, dtype, lambda o, k: glu_bwd(o, k)[0],
+        lambda o, k: f64("grad_h", o, k) * f64("up", o, k))
+    idx = sample_positions(n)
+    q = O.q(kind, synth.storage_to_f64(as_st[idx], dtype), s_all[idx])
+    stats.update({
+        "sample": int(idx.size),
+        "q_vs_exact_derivative_at_x (end to end)": error_stats(q, O.df(kind, synth.storage_to_f64(w["gate"][idx], dtype))),
+        "left_branch_share": float(s_all[idx].mean()),
     })
+    report(f"{name}/{kind}/{dtype}", stats)
