@@ -130,11 +130,15 @@ int invact_pbit_bwd(int kind, int dtype, const void* y, const void* grad_y, void
 
 /*
  * Sign-bit variant (Section 3.3, "Sign-bit Inverted Activation", and its
- * listing): no mask tensor and no change to the forward's values.  f is
- * bounded below by C = f(T), so f(x) - C is never negative and its sign bit is
- * free to carry the indicator.  The saved tensor is not the layer's output:
- * its consumer (a GEMM prologue in the paper's listing; invact_sbit_decode
- * here) first rebuilds |y_tagged| + C.
+ * listing): no mask tensor.  f is bounded below by C = f(T), so f(x) - C is
+ * never negative and its sign bit is free to carry the indicator.  The saved
+ * tensor is not the layer's output: its consumer (a GEMM prologue in the
+ * paper's listing; invact_sbit_decode here) first
+ * rebuilds |y_tagged| + C.  In real arithmetic that is f(x) again; in the
+ * storage dtype it is f(x) only to an absolute error of about one unit in
+ * the last place of C, because both f(x) - C and the sum live on the grid of
+ * max(|f(x)|, |C|): activations much smaller than |C| (x near 0) come back
+ * with few of their own digits.
  *   forward:  y_tagged[i] = max(f(x[i]) - C, 0) rounded to dtype, sign bit := (x[i] < T)
  *   decode:   y[i] = |y_tagged[i]| + C rounded to dtype
  *   backward: s_i = sign bit of y_tagged[i];  y_i = |y_tagged[i]| + C formed in binary32;

@@ -310,3 +310,26 @@ def test_gated_block_reduces_to_products(kind):
     # approximation error of q and the rounding of the stored activation
     exact = gh * up * O.df(kind, gate)
     assert np.max(np.abs(gg - exact)) <= 4e-2 * np.max(np.abs(gh * up))
+
+
+def test_point_values_can_be_regenerated_from_the_printed_formulas():
+    """tests/golden/gen_q_point_values.py (mpmath, no oracle code) reproduces every stored digit of the fixture."""
+    import importlib.util
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "gen_q_point_values.py")
+    spec = importlib.util.spec_from_file_location("gen_q_point_values", path)
+    gen = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(gen)
+    stored = {}
+    with open(os.path.join(os.path.dirname(path), "q_point_values.txt")) as fh:
+        for line in fh:
+            if line.strip() and not line.startswith("#"):
+                kind, branch, xs, value = line.split()
+                stored[(kind, branch, xs)] = value
+    assert set(stored) == set(gen.POINTS)
+    for kind, branch, xs in gen.POINTS:
+        T = gen.minimiser(kind)
+        x = T if xs == "T" else gen.M(xs)
+        value = gen.q(kind, branch, gen.F[kind](x), gen.F[kind](T))
+        text = stored[(kind, branch, xs)]
+        digits = len(text.split(".")[1])
+        assert abs(value - gen.M(text)) <= gen.M(10) ** -digits * gen.M("0.5001"), (kind, branch, xs, value, text)
