@@ -74,6 +74,8 @@ def load(path=None):
         "oracle_sbit_fwd": (None, [c_int, c_int, _dbl_p, _dbl_p, _dbl_p, c_size]),
         "oracle_sbit_decode": (None, [c_int, c_int, _dbl_p, _dbl_p, _dbl_p, c_size]),
         "oracle_sbit_bwd": (None, [c_int, _dbl_p, _dbl_p, _dbl_p, c_size]),
+        "oracle_sbit_linear": (None, [c_int, c_int, _dbl_p, _dbl_p, ctypes.c_void_p, _dbl_p, c_size, c_size, c_size]),
+        "oracle_sbit_linear_wgrad": (None, [c_int, c_int, _dbl_p, _dbl_p, _dbl_p, c_size, c_size, c_size]),
         "oracle_num_threads": (c_int, []),
     }
     for name, (res, args) in protos.items():
@@ -266,6 +268,31 @@ def sbit_bwd(kind, y_tagged, grad_y):
     gx = np.empty_like(yt)
     lib().oracle_sbit_bwd(_kind(kind), yt, g, gx, yt.size)
     return gx
+
+
+def sbit_linear(kind, dtype, y_tagged, weight, bias=None):
+    """The sign-bit layer's consumer: (|Y| + C) W^T (+ bias) -> out [M, N] (unrounded double);
+    y_tagged is [M, K], weight [N, K], bias [N] or None"""
+    yt = np.ascontiguousarray(y_tagged, dtype=np.float64); w = np.ascontiguousarray(weight, dtype=np.float64)
+    (M, K), (N, K2) = yt.shape, w.shape
+    assert K == K2
+    out = np.empty((M, N))
+    if bias is not None:
+        bias = np.ascontiguousarray(bias, dtype=np.float64)
+        assert bias.shape == (N,)
+    lib().oracle_sbit_linear(_kind(kind), _dtype(dtype), yt.reshape(-1), w.reshape(-1),
+                             None if bias is None else bias.ctypes.data, out.reshape(-1), M, N, K)
+    return out
+
+
+def sbit_linear_wgrad(kind, dtype, y_tagged, grad_out):
+    """dW = dOut^T (|Y| + C) -> [N, K] (unrounded double); y_tagged is [M, K], grad_out [M, N]"""
+    yt = np.ascontiguousarray(y_tagged, dtype=np.float64); g = np.ascontiguousarray(grad_out, dtype=np.float64)
+    (M, K), (M2, N) = yt.shape, g.shape
+    assert M == M2
+    gw = np.empty((N, K))
+    lib().oracle_sbit_linear_wgrad(_kind(kind), _dtype(dtype), yt.reshape(-1), g.reshape(-1), gw.reshape(-1), M, N, K)
+    return gw
 
 
 def num_threads():

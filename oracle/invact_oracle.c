@@ -14,7 +14,7 @@
  *   forward / backward of the layer                 Listing "forward-backward" (Algorithm 1)
  *   SwiGLU / GeGLU gated variants                   Experiments, "GeGLU" block; Limitations
  *   precision-bit variant                           Method, "Precision Bit Inverted Activation" and its listing
- *   sign-bit variant                                Method, "Sign-bit Inverted Activation" and its listing
+ *   sign-bit variant, and its consumer (Y + C) W     Method, "Sign-bit Inverted Activation" and its listing
  *
  * Pin status.  O1, O2, O3 are pinned by identities, library routines and brute
  * force (tests/test_oracle_*.py).  O4 is "parity unpinned": the paper prints
@@ -576,6 +576,42 @@ void oracle_sbit_bwd(int kind, const double *y_tagged, const double *grad_y, dou
         double y = oracle_round_scalar(DTYPE_FP32, fabs(y_tagged[i]) + C);
         grad_x[i] = grad_y[i] * q_with(&c, kind, y, s);
     }
+}
+
+/* The consumer in the paper's listing, forward: out = (Y + C) W^T (+ bias).  Y + C is what
+ * oracle_sbit_decode stores: the sum rounded to the storage dtype, which is what a matrix unit fed
+ * with that dtype multiplies.  y_tagged is [M][K], w is [N][K] (the layout of a linear layer's weight),
+ * bias is [N] or NULL, out is [M][N]; plain sums in double. */
+void oracle_sbit_linear(int kind, int dtype, const double *y_tagged, const double *w, const double *bias,
+                        double *out, size_t M, size_t N, size_t K)
+{
+    init_consts();
+    double C = fT_f32[kind];
+#pragma omp parallel for schedule(static)
+    for (size_t m = 0; m < M; ++m)
+        for (size_t n = 0; n < N; ++n) {
+            double acc = 0.0;
+            for (size_t k = 0; k < K; ++k)
+                acc += oracle_round_scalar(dtype, fabs(y_tagged[m * K + k]) + C) * w[n * K + k];
+            out[m * N + n] = bias ? acc + bias[n] : acc;
+        }
+}
+
+/* The same listing, backward: dW = dOut^T (Y + C), with Y + C as above.  grad_out is [M][N],
+ * grad_w is [N][K]. */
+void oracle_sbit_linear_wgrad(int kind, int dtype, const double *y_tagged, const double *grad_out,
+                              double *grad_w, size_t M, size_t N, size_t K)
+{
+    init_consts();
+    double C = fT_f32[kind];
+#pragma omp parallel for schedule(static)
+    for (size_t n = 0; n < N; ++n)
+        for (size_t k = 0; k < K; ++k) {
+            double acc = 0.0;
+            for (size_t m = 0; m < M; ++m)
+                acc += grad_out[m * N + n] * oracle_round_scalar(dtype, fabs(y_tagged[m * K + k]) + C);
+            grad_w[n * K + k] = acc;
+        }
 }
 
 int oracle_num_threads(void)

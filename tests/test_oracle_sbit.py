@@ -85,3 +85,51 @@ def test_backward_reads_the_sign_and_evaluates_q_at_the_rebuilt_value(kind, dtyp
     if dtype == "bf16":
         exact = g * O.df(kind, x)
         assert np.sqrt(np.mean((gx - exact) ** 2)) < np.sqrt(np.mean((ref - exact) ** 2))
+
+
+# ---------------------------------------------------------------- the consumer: (|Y| + C) W^T and dW = dOut^T (|Y| + C)
+
+def linear_case(kind, dtype, M=37, N=19, K=24, seed=5):
+    rng = np.random.default_rng(seed)
+    x = synth.storage_to_f64(synth.to_storage((rng.standard_normal(M * K) * 2.0).astype(np.float32), dtype), dtype)
+    _, yt = O.sbit_fwd(kind, dtype, x)
+    w = synth.storage_to_f64(synth.to_storage(rng.standard_normal(N * K).astype(np.float32), dtype), dtype)
+    g = synth.storage_to_f64(synth.to_storage(rng.standard_normal(M * N).astype(np.float32), dtype), dtype)
+    b = synth.storage_to_f64(synth.to_storage(rng.standard_normal(N).astype(np.float32), dtype), dtype)
+    return yt.reshape(M, K), w.reshape(N, K), g.reshape(M, N), b
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("kind", KINDS)
+def test_linear_consumer_reduces_to_the_decode(kind, dtype):
+    """With the identity as weight the product IS the decoded activation; a one-hot dOut picks one of its rows."""
+    yt, _, _, _ = linear_case(kind, dtype, K=24)
+    M, K = yt.shape
+    dec = O.sbit_decode(kind, dtype, yt.reshape(-1))[1].reshape(M, K)
+    assert np.array_equal(O.sbit_linear(kind, dtype, yt, np.eye(K)), dec)
+    assert np.array_equal(O.sbit_linear(kind, dtype, -yt, np.eye(K)), dec)          # only |Y| enters
+    for m, n in ((0, 0), (5, 3), (M - 1, 7)):
+        g = np.zeros((M, 8)); g[m, n] = 1.0
+        gw = O.sbit_linear_wgrad(kind, dtype, yt, g)
+        assert np.array_equal(gw[n], dec[m]) and np.count_nonzero(gw) == np.count_nonzero(dec[m])
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("kind", KINDS)
+def test_linear_consumer_against_a_library_product_and_its_own_adjoint(kind, dtype):
+    yt, w, g, b = linear_case(kind, dtype)
+    M, K = yt.shape
+    dec = O.sbit_decode(kind, dtype, yt.reshape(-1))[1].reshape(M, K)
+    out = O.sbit_linear(kind, dtype, yt, w, b)
+    assert np.allclose(out, dec @ w.T + b, rtol=1e-13, atol=1e-13)                  # numpy's matmul on the decoded values
+    assert np.allclose(out - O.sbit_linear(kind, dtype, yt, w), np.broadcast_to(b, out.shape), rtol=0, atol=1e-13)
+    gw = O.sbit_linear_wgrad(kind, dtype, yt, g)
+    assert np.allclose(gw, g.T @ dec, rtol=1e-13, atol=1e-13)
+    # <dOut, (Y + C) W^T> = <dOut^T (Y + C), W>: a transposed operand or a wrong index on either side breaks this
+    lhs = np.sum(g * O.sbit_linear(kind, dtype, yt, w))
+    rhs = np.sum(gw * w)
+    assert abs(lhs - rhs) <= 1e-11 * max(1.0, abs(lhs))
+    # closed form: a constant saved tensor and a weight of ones give K (c + C) rounded as the decode rounds it
+    c = float(O.round_to(dtype, np.array([0.75]))[0])
+    one = O.sbit_decode(kind, dtype, np.array([c]))[1][0]
+    assert np.allclose(O.sbit_linear(kind, dtype, np.full((3, K), -c), np.ones((2, K))), K * one, rtol=1e-14)
