@@ -23,6 +23,10 @@ bounded slice of the same workload.
 prints one line per (library build, entry point, kind, dtype, size, launch shape) instead: time per launch,
 algorithmic GB/s and the share of the 8 TB/s peak, every launch of a group on the next of enough buffer
 sets that the group's working set is at least three times the 256 MB Infinity Cache.
+
+    python bench.py --consumer M,N,K [M,N,K ...]
+
+times the sign-bit variant's fused matrix products against the decode kernel followed by torch's GEMM.
 """
 import argparse
 import json
@@ -201,6 +205,43 @@ def entry_sweep(args):
                 del bufs
 
 
+def consumer_timing(args):
+    """The sign-bit variant's consumer: the fused products against invact_sbit_decode followed by torch's GEMM
+    (hipBLASLt / rocBLAS), and torch's GEMM alone on an already decoded activation.  One line per shape M,N,K."""
+    import torch
+    from paper_2407_15545_amd import binding as B
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream()
+    kind = "gelu_erf"
+    print(f"{'M x N x K':>22s}  {'product':8s} {'fused ms':>9s} {'TFLOP/s':>8s} {'decode + GEMM ms':>17s} {'TFLOP/s':>8s} "
+          f"{'GEMM alone ms':>14s} {'TFLOP/s':>8s}", flush=True)
+    for spec in args.consumer:
+        M, N, K = (int(v) for v in spec.split(","))
+        x = torch.randn(M, K, device="cuda").bfloat16()
+        yt = B.invact_sbit_fwd(kind, x.view(-1)).view(M, K)
+        w = (torch.randn(N, K, device="cuda") * K ** -0.5).bfloat16()
+        g = torch.randn(M, N, device="cuda").bfloat16()
+        y = B.invact_sbit_decode(kind, yt.view(-1)).view(M, K)
+        out, gw, tmp = torch.empty(M, N, device="cuda", dtype=torch.bfloat16), torch.empty_like(w), torch.empty_like(y)
+        flops = 2.0 * M * N * K
+        launches = max(10, min(200, int(2e12 / flops)))
+        cases = {
+            "forward": (lambda: B.invact_sbit_linear_fwd(kind, yt, w, None, out=out),
+                        lambda: torch.mm(B.invact_sbit_decode(kind, yt.view(-1), y=tmp.view(-1)).view(M, K), w.t(), out=out),
+                        lambda: torch.mm(y, w.t(), out=out)),
+            "dW": (lambda: B.invact_sbit_linear_wgrad(kind, yt, g, grad_weight=gw),
+                   lambda: torch.mm(g.t(), B.invact_sbit_decode(kind, yt.view(-1), y=tmp.view(-1)).view(M, K), out=gw),
+                   lambda: torch.mm(g.t(), y, out=gw)),
+        }
+        for name, fns in cases.items():
+            ms = []
+            for fn in fns:
+                group_ms(torch, stream, fn, launches, 1)
+                ms.append(group_ms(torch, stream, fn, launches, 5)[0])
+            cells = "  ".join(f"{t:>12.4f} {flops / t / 1e9:8.1f}" for t in ms)
+            print(f"{M:>8d} x {N:>5d} x {K:>5d}  {name:8s} {cells}", flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -231,6 +272,9 @@ def main():
                     help="persistent grids of this many workgroups per compute unit (0 = one tile per workgroup)")
     sw.add_argument("--lib", nargs="*", default=None, help="alternative builds of libinvact.so to compare")
     sw.add_argument("--graph", action="store_true", help="time replays of a HIP graph holding the launches")
+    sw.add_argument("--consumer", nargs="+", default=None, metavar="M,N,K",
+                    help="time the sign-bit variant's fused products (forward and weight gradient) at these shapes "
+                         "against invact_sbit_decode + torch's GEMM")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: the path is element-wise and needs no exchange between GPUs, "
@@ -248,6 +292,8 @@ def main():
     if not os.path.exists(hip_build.LIB):               # nothing built yet: build, never fall back
         hip_build.build(force=True)
     B.lib()                                              # fails loudly if the HIP library is missing
+    if args.consumer:
+        return consumer_timing(args)
     if args.entries is not None:
         if not (args.log2_sizes or args.elements_list):
             args.log2_sizes = [26, 28]

@@ -133,7 +133,8 @@ int invact_pbit_bwd(int kind, int dtype, const void* y, const void* grad_y, void
  * listing): no mask tensor.  f is bounded below by C = f(T), so f(x) - C is
  * never negative and its sign bit is free to carry the indicator.  The saved
  * tensor is not the layer's output: its consumer (a GEMM prologue in the
- * paper's listing; invact_sbit_decode here) first
+ * paper's listing; invact_sbit_decode, or the two
+ * invact_sbit_linear_* products below) first
  * rebuilds |y_tagged| + C.  In real arithmetic that is f(x) again; in the
  * storage dtype it is f(x) only to an absolute error of about one unit in
  * the last place of C, because both f(x) - C and the sum live on the grid of
@@ -150,6 +151,27 @@ int invact_sbit_fwd(int kind, int dtype, const void* x, void* y_tagged, size_t n
 int invact_sbit_decode(int kind, int dtype, const void* y_tagged, void* y, size_t n, hipStream_t stream);
 int invact_sbit_bwd(int kind, int dtype, const void* y_tagged, const void* grad_y, void* grad_x,
                     size_t n, hipStream_t stream);
+
+/*
+ * Sign-bit variant, the consumer (Section 3.3 and its listing: "return (Y + C) @ W_linear" in
+ * the forward, "dW = (Y + C)^T @ dOut" in the backward): matrix products that rebuild
+ * |y_tagged| + C while they load the saved tensor, so that the activation itself is never
+ * written to memory.  bfloat16 only (INVACT_ERR_DTYPE otherwise); products on the matrix
+ * units with binary32 accumulation, |y_tagged| + C rounded to bfloat16 exactly as
+ * invact_sbit_decode rounds it, one rounding of each output element to bfloat16.
+ *   invact_sbit_linear_fwd:    out[m][n]         = sum_k (|y_tagged[m][k]| + C) * weight[n][k]  (+ bias[n])
+ *   invact_sbit_linear_wgrad:  grad_weight[n][k] = sum_m grad_out[m][n] * (|y_tagged[m][k]| + C)
+ * y_tagged: in, M x K.  weight: in, N x K (the layout of a linear layer's weight).  bias: in,
+ * N elements, or NULL.  out, grad_out: M x N.  grad_weight: out, N x K.  All row-major and
+ * dense.  K must be a multiple of 64 for the forward, M a multiple of 64 for the weight
+ * gradient, and every matrix must hold fewer than 2^31 elements (INVACT_ERR_SIZE otherwise;
+ * M or N equal to 0 succeeds without a launch).  Matrix pointers must be 16-byte aligned.
+ * No aliasing between an output and an input.
+ */
+int invact_sbit_linear_fwd(int kind, int dtype, const void* y_tagged, const void* weight, const void* bias,
+                           void* out, size_t M, size_t N, size_t K, hipStream_t stream);
+int invact_sbit_linear_wgrad(int kind, int dtype, const void* y_tagged, const void* grad_out,
+                             void* grad_weight, size_t M, size_t N, size_t K, hipStream_t stream);
 
 /*
  * Launch tuning (process-wide, for benchmarking; results are bit-identical

@@ -33,6 +33,8 @@ _PROTOTYPES = {
     "invact_sbit_fwd": (_int, [_int, _int, _vp, _vp, _sz, _vp]),
     "invact_sbit_decode": (_int, [_int, _int, _vp, _vp, _sz, _vp]),
     "invact_sbit_bwd": (_int, [_int, _int, _vp, _vp, _vp, _sz, _vp]),
+    "invact_sbit_linear_fwd": (_int, [_int, _int, _vp, _vp, _vp, _vp, _sz, _sz, _sz, _vp]),
+    "invact_sbit_linear_wgrad": (_int, [_int, _int, _vp, _vp, _vp, _sz, _sz, _sz, _vp]),
     "swiglu_invact_fwd": (_int, [_int, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "swiglu_invact_bwd": (_int, [_int, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
 }
@@ -244,3 +246,48 @@ def swiglu_invact_bwd(act, up, mask, grad_h, grad_gate=None, grad_up=None, strea
         _check(lib().swiglu_invact_bwd(dt, act.data_ptr(), up.data_ptr(), mask.data_ptr(), grad_h.data_ptr(),
                                        grad_gate.data_ptr(), grad_up.data_ptr(), n, _stream(stream)))
     return grad_gate, grad_up
+
+
+def _matrices(*ts):
+    """dtype code and device of 2-D dense tensors that one call multiplies."""
+    first = ts[0]
+    for t in ts:
+        if not (t.is_cuda and t.is_contiguous() and t.dim() == 2):
+            raise ValueError("matrices must be contiguous 2-D CUDA tensors")
+        if t.dtype != first.dtype or t.device != first.device:
+            raise ValueError("matrices of one call must share dtype and device")
+    if first.dtype not in DTYPES:
+        raise ValueError(f"unsupported dtype {first.dtype}")
+    return DTYPES[first.dtype]
+
+
+def invact_sbit_linear_fwd(kind, y_tagged, weight, bias=None, out=None, stream=None):
+    """out = (|y_tagged| + C) weight^T (+ bias): y_tagged [M, K], weight [N, K], bias [N] or None.  Returns out [M, N]."""
+    (M, K), (N, K2) = y_tagged.shape, weight.shape
+    if K != K2 or (bias is not None and (bias.shape != (N,) or bias.dtype != weight.dtype or not bias.is_contiguous())):
+        raise ValueError("weight must be [N, K] and bias a contiguous [N] of the same dtype")
+    out = torch.empty((M, N), dtype=y_tagged.dtype, device=y_tagged.device) if out is None else out
+    dt = _matrices(y_tagged, weight, out)
+    if out.shape != (M, N):
+        raise ValueError("out must be [M, N]")
+    with _on_device(y_tagged.device):
+        _check(lib().invact_sbit_linear_fwd(_kind(kind), dt, y_tagged.data_ptr(), weight.data_ptr(),
+                                            None if bias is None else bias.data_ptr(), out.data_ptr(), M, N, K,
+                                            _stream(stream)))
+    return out
+
+
+def invact_sbit_linear_wgrad(kind, y_tagged, grad_out, grad_weight=None, stream=None):
+    """grad_weight = grad_out^T (|y_tagged| + C): y_tagged [M, K], grad_out [M, N].  Returns grad_weight [N, K]."""
+    (M, K), (M2, N) = y_tagged.shape, grad_out.shape
+    if M != M2:
+        raise ValueError("y_tagged and grad_out must have the same number of rows")
+    if grad_weight is None:
+        grad_weight = torch.empty((N, K), dtype=y_tagged.dtype, device=y_tagged.device)
+    dt = _matrices(y_tagged, grad_out, grad_weight)
+    if grad_weight.shape != (N, K):
+        raise ValueError("grad_weight must be [N, K]")
+    with _on_device(y_tagged.device):
+        _check(lib().invact_sbit_linear_wgrad(_kind(kind), dt, y_tagged.data_ptr(), grad_out.data_ptr(),
+                                              grad_weight.data_ptr(), M, N, K, _stream(stream)))
+    return grad_weight

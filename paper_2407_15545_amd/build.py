@@ -4,9 +4,10 @@ import subprocess
 import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SRC = os.path.join(HERE, "csrc", "invact_kernels.hip")
-DEPS = [SRC, os.path.join(HERE, "csrc", "invact_math.h"), os.path.join(HERE, "csrc", "invact_constants.h"),
-        os.path.join(os.path.dirname(HERE), "include", "invact.h")]
+SRCS = [os.path.join(HERE, "csrc", "invact_kernels.hip"),      # the element-wise kernels and their C ABI
+        os.path.join(HERE, "csrc", "invact_gemm.hip")]         # the sign-bit variant's fused consumer (MFMA GEMMs)
+DEPS = SRCS + [os.path.join(HERE, "csrc", "invact_math.h"), os.path.join(HERE, "csrc", "invact_constants.h"),
+               os.path.join(os.path.dirname(HERE), "include", "invact.h")]
 LIB = os.path.join(HERE, "libinvact.so")
 
 HIPCC_FLAGS = [
@@ -26,7 +27,7 @@ def build(force=True, verbose=False, extra=(), out=LIB):
     if not force and out == LIB and up_to_date():
         return LIB
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, *extra, "-o", out, SRC]
+    cmd = [hipcc, *HIPCC_FLAGS, *extra, "-o", out, *SRCS]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)

@@ -108,13 +108,21 @@ class _InvActGLU(torch.autograd.Function):
 
 class _SignBitActLinear(torch.autograd.Function):
     """Activation followed by a linear layer, sign-bit variant (Section 3.3 and its listing): the only
-    saved activation is f(x) - min f with the indicator in its sign bit; f(x) itself is rebuilt when
-    the matrix products need it and dropped again."""
+    saved activation is f(x) - min f with the indicator in its sign bit.  In bfloat16, with shapes the fused
+    products take (in_features a multiple of 64; for the weight gradient a token count that is a multiple of
+    64 and out_features a multiple of 8), f(x) is rebuilt inside the two matrix products and never exists in
+    memory; otherwise invact_sbit_decode rebuilds it for a library GEMM and it is dropped again."""
 
     @staticmethod
     def forward(ctx, x, weight, bias, kind):
-        y_tagged = B.invact_sbit_fwd(kind, _dense(x))
-        out = torch.nn.functional.linear(B.invact_sbit_decode(kind, y_tagged).view_as(x), weight, bias)
+        y_tagged = B.invact_sbit_fwd(kind, _dense(x)).view(-1, weight.shape[1])
+        M, K = y_tagged.shape
+        w = _dense(weight)
+        if x.dtype == torch.bfloat16 and weight.dtype == torch.bfloat16 and K % 64 == 0 and M > 0:
+            b = None if bias is None else bias.to(torch.bfloat16).contiguous()
+            out = B.invact_sbit_linear_fwd(kind, y_tagged, w, b).view(*x.shape[:-1], weight.shape[0])
+        else:
+            out = torch.nn.functional.linear(B.invact_sbit_decode(kind, y_tagged.view(-1)).view_as(x), weight, bias)
         ctx.kind, ctx.has_bias = kind, bias is not None
         ctx.save_for_backward(y_tagged, weight)
         return out
@@ -122,12 +130,16 @@ class _SignBitActLinear(torch.autograd.Function):
     @staticmethod
     def backward(ctx, grad_out):
         y_tagged, weight = ctx.saved_tensors
-        g2 = grad_out.reshape(-1, grad_out.shape[-1])
-        y2 = B.invact_sbit_decode(ctx.kind, y_tagged).view(-1, weight.shape[1])
-        grad_w = g2.t().mm(y2)
+        M, K = y_tagged.shape
+        N = weight.shape[0]
+        g2 = _dense(grad_out.reshape(-1, N))
+        if y_tagged.dtype == torch.bfloat16 and g2.dtype == torch.bfloat16 and M % 64 == 0 and N % 8 == 0 and K % 8 == 0 and M > 0:
+            grad_w = B.invact_sbit_linear_wgrad(ctx.kind, y_tagged, g2).to(weight.dtype)
+        else:
+            grad_w = g2.t().mm(B.invact_sbit_decode(ctx.kind, y_tagged.view(-1)).view(M, K))
         grad_b = g2.sum(0) if ctx.has_bias else None
         grad_y = _dense(g2.mm(weight))
-        grad_x = B.invact_sbit_bwd(ctx.kind, y_tagged.view(-1), grad_y.view(-1)).view(y_tagged.shape)
+        grad_x = B.invact_sbit_bwd(ctx.kind, y_tagged.view(-1), grad_y.view(-1)).view(*grad_out.shape[:-1], K)
         return grad_x, grad_w, grad_b, None
 
 

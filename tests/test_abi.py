@@ -74,6 +74,20 @@ def test_argument_validation_happens_before_any_launch():
     assert lib.invact_pbit_fwd(0, 1, a8, a16, 8, None) == ERR_ALIGN
     assert lib.invact_pbit_bwd(3, 1, a16, a16, a16, 8, None) == ERR_KIND
     assert lib.invact_pbit_bwd(0, 1, a16, a16, a16, 0, None) == OK
+    lin, wg = lib.invact_sbit_linear_fwd, lib.invact_sbit_linear_wgrad
+    assert lin(5, 1, a16, a16, None, a16, 128, 128, 64, None) == ERR_KIND
+    assert lin(1, 0, a16, a16, None, a16, 128, 128, 64, None) == ERR_DTYPE          # bfloat16 only
+    assert lin(1, 1, a16, a16, None, a16, 128, 128, 65, None) == ERR_SIZE           # K in whole steps of 64
+    assert lin(1, 1, a16, a16, None, a16, 1 << 20, 128, 1 << 12, None) == ERR_SIZE  # 2^32 elements
+    assert lin(1, 1, None, a16, None, a16, 128, 128, 64, None) == ERR_NULL
+    assert lin(1, 1, a16, a8, None, a16, 128, 128, 64, None) == ERR_ALIGN
+    assert lin(1, 1, a16, a16, None, a16, 0, 128, 64, None) == OK
+    assert wg(1, 1, a16, a16, a16, 100, 128, 64, None) == ERR_SIZE                  # M in whole steps of 64
+    assert wg(1, 1, a16, a16, a16, 128, 100, 64, None) == ERR_SIZE                  # N, K multiples of 8
+    assert wg(1, 0, a16, a16, a16, 128, 128, 64, None) == ERR_DTYPE
+    assert wg(1, 1, a16, None, a16, 128, 128, 64, None) == ERR_NULL
+    assert wg(1, 1, a16, a16, odd, 128, 128, 64, None) == ERR_ALIGN
+    assert wg(1, 1, a16, a16, a16, 128, 0, 64, None) == OK
     # n == 0 is a successful no-op, whatever the pointers
     assert fwd(0, 0, None, None, None, 0, None) == OK
     assert bwd(2, 1, None, None, None, None, 0, None) == OK

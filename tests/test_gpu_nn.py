@@ -195,15 +195,19 @@ def test_block_bench_blocks_match_torch_and_time():
         assert BB.time_block(BB.Plain(inv.InvActGELU()), xs, iters=3, groups=2, graph=graph) > 0
 
 
+@pytest.mark.parametrize("shape, dtype", [((512, 1024), torch.bfloat16),        # both products fused
+                                          ((4, 96, 512), torch.bfloat16),        # 3-D input, fused
+                                          ((100, 1000), torch.bfloat16),         # shapes the fused products refuse
+                                          ((512, 1024), torch.float32)])         # binary32: decode + library GEMM
 @pytest.mark.parametrize("kind", ["gelu_erf", "silu"])
-def test_sign_bit_act_linear_matches_torch_and_saves_one_tensor(kind, wiring):
+def test_sign_bit_act_linear_matches_torch_and_saves_one_tensor(kind, shape, dtype, wiring):
     if wiring != "python":
         pytest.skip("the sign-bit layer has one wiring")
     torch.manual_seed(3)
-    tokens, d_in, d_out = 512, 1024, 256
-    x = torch.randn(tokens, d_in, device="cuda", dtype=torch.bfloat16, requires_grad=True)
-    layer = inv.SignBitActLinear(d_in, d_out, kind=kind, device="cuda", dtype=torch.bfloat16)
-    PT.say(f"nn sign-bit act + linear {kind}")
+    d_in, d_out = shape[-1], 256
+    x = torch.randn(*shape, device="cuda", dtype=dtype, requires_grad=True)
+    layer = inv.SignBitActLinear(d_in, d_out, kind=kind, device="cuda", dtype=dtype)
+    PT.say(f"nn sign-bit act + linear {kind} {shape} {dtype}")
     out = layer(x)
     ref = F.linear(REFS[kind](x), layer.weight, layer.bias)
     assert torch.allclose(out.float(), ref.float(), rtol=3e-2, atol=3e-2)
@@ -215,9 +219,9 @@ def test_sign_bit_act_linear_matches_torch_and_saves_one_tensor(kind, wiring):
     # saved: the tagged tensor (same size as x) and the weight; torch keeps x, f(x) and the weight
     ours = inv.saved_activation_bytes(lambda: layer(x))[0]
     base = inv.saved_activation_bytes(lambda: F.linear(REFS[kind](x), layer.weight, layer.bias))[0]
-    weight_bytes = layer.weight.numel() * 2
-    assert ours - weight_bytes == x.numel() * 2
-    assert base - weight_bytes == 2 * x.numel() * 2
+    weight_bytes = layer.weight.numel() * x.element_size()
+    assert ours - weight_bytes == x.numel() * x.element_size()
+    assert base - weight_bytes == 2 * x.numel() * x.element_size()
 
 
 def test_whole_model_memory_saving_matches_the_papers_table(wiring):

@@ -156,3 +156,87 @@ def test_sbit_round_trip_rebuilds_the_activation_to_the_grid_of_the_stored_value
         worse = np.abs(PT.to_f64(y) - f)[small].max() / np.abs(PT.to_f64(y_plain) - f)[small].max()
         PT.say(f"sign-bit round trip {dtype}: largest error where |f| < 2^-6 is {worse:.0f} x that of invact_fwd")
         assert worse > 4
+
+
+# ---------------------------------------------------------------- the consumer: matrix products that decode on load
+
+def linear_inputs(kind, M, N, K, seed):
+    """Saved tensor of a sign-bit forward on N(0, 2^2) inputs, a weight ~ N(0, 1/K), dOut ~ N(0, 1), bias ~ N(0, 1),
+    all bfloat16; returns storage arrays and their float64 values."""
+    x = synth.to_storage(synth.normal(M * K, seed, 2.0), "bf16")
+    _, yt64 = O.sbit_fwd(kind, "bf16", synth.storage_to_f64(x, "bf16"))
+    st = {"yt": synth.f64_to_storage_exact(yt64, "bf16").reshape(M, K),
+          "w": synth.to_storage(synth.normal(N * K, seed + 1, K ** -0.5), "bf16").reshape(N, K),
+          "g": synth.to_storage(synth.normal(M * N, seed + 2, 1.0), "bf16").reshape(M, N),
+          "b": synth.to_storage(synth.normal(N, seed + 3, 1.0), "bf16")}
+    return st, {k: synth.storage_to_f64(v.reshape(-1), "bf16").reshape(v.shape) for k, v in st.items()}
+
+
+def product_errors(gpu, ref, abs_sum, terms):
+    """Error of a bfloat16 output of a product accumulated in binary32, in units of the tolerance:
+    2 bfloat16 ulp of the reference for the final rounding, plus (terms + 2) 2^-24 times the sum of the
+    absolute values of the terms for the accumulation in any order."""
+    tol = 2.0 * PT.ulp(ref, "bf16") + (terms + 2) * 2.0 ** -24 * abs_sum
+    return np.abs(gpu - ref) / tol
+
+
+LINEAR_SHAPES = [(128, 128, 64), (256, 384, 192), (200, 136, 128), (72, 264, 320), (1, 8, 64), (130, 8, 64)]
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_linear_forward_decodes_while_it_loads(kind):
+    for M, N, K in LINEAR_SHAPES:
+        PT.say(f"invact_sbit_linear_fwd {kind} M={M} N={N} K={K}")
+        st, v = linear_inputs(kind, M, N, K, 900 + M)
+        dev = {k: PT.to_device(a.reshape(-1), "bf16").view(a.shape) for k, a in st.items()}
+        dec = O.sbit_decode(kind, "bf16", v["yt"].reshape(-1))[1].reshape(M, K)
+        abs_sum = np.abs(dec) @ np.abs(v["w"]).T
+        for bias in (None, "b"):
+            ref = O.sbit_linear(kind, "bf16", v["yt"], v["w"], None if bias is None else v["b"])
+            out = B.invact_sbit_linear_fwd(kind, dev["yt"], dev["w"], None if bias is None else dev["b"])
+            torch.cuda.synchronize()
+            got = PT.to_f64(out.reshape(-1)).reshape(M, N)
+            e = product_errors(got, ref, abs_sum + (0 if bias is None else np.abs(v["b"])), K)
+            assert e.max() <= 1.0, (M, N, K, bias, np.unravel_index(np.argmax(e), e.shape), e.max())
+        # and it agrees with the separate route (decode kernel, then a binary32 product of the decoded values
+        # plus the bias) to the same tolerance
+        y = B.invact_sbit_decode(kind, dev["yt"].view(-1)).view(M, K)
+        two_step = (y.float() @ dev["w"].float().t() + dev["b"].float()).double().cpu().numpy()
+        assert np.max(np.abs(got - two_step) / (2.0 * PT.ulp(two_step, "bf16") + (K + 2) * 2.0 ** -24 * abs_sum)) <= 1.0
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_linear_weight_gradient_decodes_while_it_loads(kind):
+    for M, N, K in [(64, 128, 128), (192, 384, 256), (128, 136, 200), (320, 72, 264), (64, 8, 8), (64, 8, 136)]:
+        PT.say(f"invact_sbit_linear_wgrad {kind} M={M} N={N} K={K}")
+        st, v = linear_inputs(kind, M, N, K, 950 + K)
+        dev = {k: PT.to_device(a.reshape(-1), "bf16").view(a.shape) for k, a in st.items()}
+        dec = O.sbit_decode(kind, "bf16", v["yt"].reshape(-1))[1].reshape(M, K)
+        ref = O.sbit_linear_wgrad(kind, "bf16", v["yt"], v["g"])
+        gw = B.invact_sbit_linear_wgrad(kind, dev["yt"], dev["g"])
+        torch.cuda.synchronize()
+        got = PT.to_f64(gw.reshape(-1)).reshape(N, K)
+        e = product_errors(got, ref, np.abs(v["g"]).T @ np.abs(dec), M)
+        assert e.max() <= 1.0, (M, N, K, np.unravel_index(np.argmax(e), e.shape), e.max())
+
+
+def test_linear_at_a_transformer_block_size_on_sampled_outputs():
+    """4096 tokens of a 1024 -> 4096 -> 1024 block (the shape of the paper's MLP-block timing, a batch the oracle
+    can follow): 2^14 sampled outputs of either product against the oracle's sums over their own rows and columns."""
+    kind, M, N, K = "gelu_erf", 4096, 1024, 4096
+    PT.say(f"invact_sbit_linear fwd/wgrad {kind} M={M} N={N} K={K}, sampled")
+    st, v = linear_inputs(kind, M, N, K, 77)
+    dev = {k: PT.to_device(a.reshape(-1), "bf16").view(a.shape) for k, a in st.items()}
+    dec = O.sbit_decode(kind, "bf16", v["yt"].reshape(-1))[1].reshape(M, K)
+    out = PT.to_f64(B.invact_sbit_linear_fwd(kind, dev["yt"], dev["w"], dev["b"]).reshape(-1)).reshape(M, N)
+    gw = PT.to_f64(B.invact_sbit_linear_wgrad(kind, dev["yt"], dev["g"]).reshape(-1)).reshape(N, K)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(3)
+    rows, cols = rng.integers(0, M, 128), rng.integers(0, N, 128)
+    ref = O.sbit_linear(kind, "bf16", v["yt"][rows], v["w"][cols], v["b"][cols])            # 128 x 128 outputs
+    e = product_errors(out[np.ix_(rows, cols)], ref, np.abs(dec[rows]) @ np.abs(v["w"][cols]).T + np.abs(v["b"][cols]), K)
+    assert e.max() <= 1.0, e.max()
+    ns, ks = rng.integers(0, N, 128), rng.integers(0, K, 128)
+    ref = O.sbit_linear_wgrad(kind, "bf16", v["yt"][:, ks], v["g"][:, ns])
+    e = product_errors(gw[np.ix_(ns, ks)], ref, np.abs(v["g"][:, ns]).T @ np.abs(dec[:, ks]), M)
+    assert e.max() <= 1.0, e.max()
