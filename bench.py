@@ -233,13 +233,16 @@ def consumer_timing(args):
                    lambda: torch.mm(g.t(), B.invact_sbit_decode(kind, yt.view(-1), y=tmp.view(-1)).view(M, K), out=gw),
                    lambda: torch.mm(g.t(), y, out=gw)),
         }
-        for name, fns in cases.items():
-            ms = []
-            for fn in fns:
-                group_ms(torch, stream, fn, launches, 1)
-                ms.append(group_ms(torch, stream, fn, launches, 5)[0])
-            cells = "  ".join(f"{t:>12.4f} {flops / t / 1e9:8.1f}" for t in ms)
-            print(f"{M:>8d} x {N:>5d} x {K:>5d}  {name:8s} {cells}", flush=True)
+        for tile in args.linear_tile:
+            B.set_linear_tile(tile)
+            for name, fns in cases.items():
+                ms = []
+                for fn in fns if tile == args.linear_tile[0] else fns[:1]:
+                    group_ms(torch, stream, fn, launches, 1)
+                    ms.append(group_ms(torch, stream, fn, launches, 5)[0])
+                cells = "  ".join(f"{t:>12.4f} {flops / t / 1e9:8.1f}" for t in ms)
+                print(f"{M:>8d} x {N:>5d} x {K:>5d}  {name:8s} {cells}" + (f"   [tile {tile}]" if tile else ""), flush=True)
+        B.set_linear_tile(0)
 
 
 def main():
@@ -275,6 +278,8 @@ def main():
     sw.add_argument("--consumer", nargs="+", default=None, metavar="M,N,K",
                     help="time the sign-bit variant's fused products (forward and weight gradient) at these shapes "
                          "against invact_sbit_decode + torch's GEMM")
+    sw.add_argument("--linear-tile", type=int, nargs="+", default=[0], choices=[0, 2, 4],
+                    help="with --consumer: force the fused products' workgroup tile (4: 256 x 256, 2: 128 x 128, 0: the library's choice)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: the path is element-wise and needs no exchange between GPUs, "

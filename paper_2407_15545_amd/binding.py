@@ -24,6 +24,7 @@ _PROTOTYPES = {
     "invact_strerror": (ctypes.c_char_p, [_int]),
     "invact_set_blocks_per_cu": (_int, [_int]),
     "invact_set_resident_blocks": (_int, [_int]),
+    "invact_set_linear_tile": (_int, [_int]),
     "invact_fwd": (_int, [_int, _int, _vp, _vp, _vp, _sz, _vp]),
     "invact_bwd": (_int, [_int, _int, _vp, _vp, _vp, _vp, _sz, _vp]),
     "geglu_invact_fwd": (_int, [_int, _int, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
@@ -246,6 +247,12 @@ def swiglu_invact_bwd(act, up, mask, grad_h, grad_gate=None, grad_up=None, strea
         _check(lib().swiglu_invact_bwd(dt, act.data_ptr(), up.data_ptr(), mask.data_ptr(), grad_h.data_ptr(),
                                        grad_gate.data_ptr(), grad_up.data_ptr(), n, _stream(stream)))
     return grad_gate, grad_up
+
+
+def set_linear_tile(t):
+    """Tile of the fused sign-bit products: 4 (256 x 256), 2 (128 x 128) or 0 (chosen by the output's size)."""
+    if lib().invact_set_linear_tile(int(t)) < 0:
+        raise ValueError("tile must be 0, 2 or 4")
 
 
 def _matrices(*ts):
