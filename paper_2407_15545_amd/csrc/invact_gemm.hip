@@ -220,8 +220,11 @@ __global__ __launch_bounds__(S::kThreads) void sbit_linear_wgrad_kernel(const ui
     const unsigned t = threadIdx.x, lane = t & 63u, wave = t >> 6;
     const unsigned wm = (wave / S::WN) * (32 * S::TM), wn = (wave % S::WN) * (32 * S::TN);
 
-    // loader: thread t moves one piece (8 columns) of rows 2 pair, 2 pair + 1 (+ 2 kPairs, ...) of either operand tile
-    const unsigned pair_g = t / kPiecesG, piece_g = t % kPiecesG, pair_a = t / kPiecesA, piece_a = t % kPiecesA;
+    // loader: thread t moves one piece (8 columns) of rows 2 pair, 2 pair + 1 (+ 2 kPairs, ...) of either operand tile.
+    // A wavefront takes 16 neighbouring pieces of 4 neighbouring row pairs: its 64 scattered 32-bit LDS writes
+    // (one element index e at a time) then fall on all 32 banks twice over, which is as good as 256 bytes get.
+    const unsigned pair_g = (wave / (kPiecesG / 16)) * 4u + (lane >> 4), piece_g = (lane & 15u) + 16u * (wave % (kPiecesG / 16));
+    const unsigned pair_a = (wave / (kPiecesA / 16)) * 4u + (lane >> 4), piece_a = (lane & 15u) + 16u * (wave % (kPiecesA / 16));
     const __amdgpu_buffer_rsrc_t g_src = whole_buffer(grad_out, M * N * 2u), a_src = whole_buffer(y_tagged, M * K * 2u);
     const bool g_in = n0 + piece_g * 8u < N, a_in = k0 + piece_a * 8u < K;  // N and K are multiples of 8: a piece is in or out
     const unsigned g_off = (2u * pair_g * N + n0 + piece_g * 8u) * 2u, a_off = (2u * pair_a * K + k0 + piece_a * 8u) * 2u;
