@@ -8,19 +8,18 @@
 // from global memory to LDS.  The decoded activation never exists in HBM: against invact_sbit_decode
 // followed by a library GEMM that saves one read and one write of the activation per product.
 //
-// Shape of both kernels.  A workgroup of 256 threads (2 x 2 wavefronts) owns a 128 x 128 tile of the
-// output; each wavefront a 64 x 64 quarter as 2 x 2 MFMA tiles of 32 x 32.  The contraction runs in steps
-// of 64: both operand tiles (128 x 64 bfloat16 each) are loaded with coalesced 128-bit buffer loads into
-// registers one step ahead, written to one of two LDS buffers (rows padded to 144 bytes, which spreads the
-// 128-bit fragment reads over the banks), and one barrier per step separates the writer of a buffer from
-// its readers.  Rows and columns outside the matrices are handled by the buffer extents (loads return 0,
-// which the decode turns into C times an operand that is 0; the rows are never stored) and by a column
-// test at the store.  Workgroup indices are remapped so that the workgroups an XCD receives (every
-// eighth one) are neighbours in the output and share their operand tiles in that XCD's L2.
+// Shape of both kernels.  A workgroup owns a tile of the output (256 x 256 with 8 wavefronts of 128 x 64, or
+// one of the other shapes below); each wavefront a block of TM x TN MFMA tiles of 32 x 32.  The contraction
+// runs in steps of 64 as a software pipeline of depth two (see contract): operand tiles travel global memory
+// -> registers -> (decode) -> one of two LDS buffers -> MFMA fragments, and the work of all four stages is
+// spread between the MFMAs of a step.  Rows and columns outside the matrices are handled by the buffer
+// extents (loads return 0, stores are dropped).  Workgroup indices are remapped so that the workgroups an XCD
+// receives (every eighth one) are neighbours in the output and share their operand tiles in that XCD's L2.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
 #include <atomic>
+#include <utility>
 
 #include "../../include/invact.h"
 #include "invact_constants.h"
@@ -29,10 +28,12 @@ namespace {
 
 namespace cst = invact_const;
 
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16   bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16   bf16x2 __attribute__((ext_vector_type(2)));
 typedef float    f32x2 __attribute__((ext_vector_type(2)));
+typedef float    f32x4 __attribute__((ext_vector_type(4)));
 typedef float    f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int kStep = 64;               // contraction elements per step
@@ -48,7 +49,10 @@ template <int TM_, int TN_, int WM_, int WN_> struct Shape {
     static constexpr int TM = TM_, TN = TN_, WM = WM_, WN = WN_;
     static constexpr int kThreads = 64 * WM * WN;
     static constexpr int kTileM = 32 * TM * WM, kTileN = 32 * TN * WN;      // rows of the two operand tiles
-    static constexpr unsigned kLdsBytes = 2 /* buffers */ * (kTileM + kTileN) * kRow * 2;
+    static constexpr unsigned kOperandBytes = 2 /* buffers */ * (kTileM + kTileN) * kRow * 2;
+    static constexpr unsigned kStagingBytes = WM * WN * (32 * TM) * (32 * TN + 8) * 2;      // the output, on its way out
+    static_assert(kStagingBytes <= kOperandBytes, "the output is staged in the operand buffers");
+    static constexpr unsigned kLdsBytes = kOperandBytes + kTileN * 4;                       // and the bias behind them
 };
 using Large = Shape<4, 2, 2, 4>;
 using Small = Shape<2, 2, 2, 2>;
@@ -63,24 +67,25 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t whole_buffer(const void* p, un
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
 }
 
+constexpr unsigned kOutside = 0xFFFFFFF0u;      // a byte offset past the extent of every buffer here
+
 __device__ __forceinline__ uint32_t pack2(float lo, float hi)          // round to nearest even (v_cvt_pk_bf16_f32)
 {
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo, hi}, bf16x2));
 }
 
-// |y| + C on 8 bfloat16 values: the sum is formed in binary32 and rounded once to bfloat16, exactly as
+// |y| + C on two (eight) bfloat16 values: the sum is formed in binary32 and rounded once to bfloat16, exactly as
 // invact_sbit_decode forms it.
+template <int KIND>
+__device__ __forceinline__ uint32_t decode2(uint32_t v)
+{
+    constexpr float C = min_of_kind<KIND>();
+    return pack2(__builtin_fabsf(__uint_as_float(v << 16)) + C, __builtin_fabsf(__uint_as_float(v & 0xFFFF0000u)) + C);
+}
 template <int KIND>
 __device__ __forceinline__ u32x4 decode8(u32x4 v)
 {
-    constexpr float C = min_of_kind<KIND>();
-    u32x4 out;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const uint32_t w = v[j] & 0x7FFF7FFFu;
-        out[j] = pack2(__uint_as_float(w << 16) + C, __uint_as_float(w & 0xFFFF0000u) + C);
-    }
-    return out;
+    return u32x4{decode2<KIND>(v[0]), decode2<KIND>(v[1]), decode2<KIND>(v[2]), decode2<KIND>(v[3])};
 }
 
 // Consecutive workgroup indices land on different XCDs (eight of them).  Give XCD x the x-th eighth of the
@@ -91,33 +96,224 @@ __device__ __forceinline__ unsigned xcd_contiguous(unsigned block, unsigned bloc
     return (blocks % 8u) ? block : (block % 8u) * (blocks / 8u) + block / 8u;
 }
 
-// One contraction step of a wavefront: 4 sub-steps of 16, each reading two fragments of either operand
-// (lane l: row l % 32 of the 32-row tile, elements 8 (l / 32) .. + 7 of the sub-step) and issuing 2 x 2 MFMAs.
-// SWIZZLED: the 16-byte pieces of LDS row R sit at position (piece ^ (R / 8 % 8)), which is how the
-// transposing loader of the weight-gradient kernel keeps its scattered writes off each other's banks
-// (a wavefront's offset into a tile is a multiple of 64 rows, so R / 8 % 8 is that of the row inside its part).
-template <bool SWIZZLED, int TM, int TN>
-__device__ __forceinline__ void mfma_step(const uint16_t* a_tile, const uint16_t* b_tile, unsigned lane, f32x16 (&acc)[TM][TN])
+// Compile-time loops: f(std::integral_constant<int, FIRST>) ... f(std::integral_constant<int, LAST - 1>).
+template <int FIRST, int... Is, class F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, Is...>, F&& f)
 {
+    (f(std::integral_constant<int, FIRST + Is>{}), ...);
+}
+template <int FIRST, int LAST, class F> __device__ __forceinline__ void static_for(F&& f)
+{
+    if constexpr (LAST > FIRST) static_for_impl<FIRST>(std::make_integer_sequence<int, LAST - FIRST>{}, f);
+}
+// The I-th of N equal shares of COUNT items: [share_begin, share_end).
+template <int I, int N, int COUNT> constexpr int share_begin = I * COUNT / N;
+template <int I, int N, int COUNT> constexpr int share_end = (I + 1) * COUNT / N;
+
+// The contraction loop of both products.  LDS holds two buffers of either operand tile ([rows][kRow], a row is
+// a row or column of the output, its elements one step of the contraction); a wavefront accumulates
+// acc[i][j] += B-tile j x A-tile i (the MFMA gets the column operand first: see store_accumulators).
+//
+// A software pipeline of depth two.  During step s a wavefront
+//   * multiplies out of buffer s % 2, reading the fragments of sub-step kk + 1 (of four) while the MFMAs of kk run,
+//   * writes the operand tiles of step s + 1, which its registers hold since step s - 1, into the other buffer,
+//   * and loads the tiles of step s + 2 into the registers this frees, piece by piece, so that every load has a
+//     whole step to arrive.
+// The loader supplies the last two as tasks: kTasks0, kTasks1, kTasks2 of them for the first three sub-steps,
+// task<KK, T>(a_next, b_next, s + 2).  After each MFMA comes its share of the sub-step's other work, and the
+// compiler is kept from moving anything across (left alone it gathers the MFMAs, and the matrix unit idles
+// while the wavefront decodes and stages).  One barrier per step, before the last sub-step: by then every
+// wavefront has read all of buffer s % 2 and written all of the other one, and the last sub-step fetches the
+// first fragments of step s + 1.  The steps past the end of the contraction that the pipeline's tail asks for
+// are reloads of the last one and are never multiplied.
+//
+// SWIZZLED: the 16-byte pieces of LDS row R sit at position (piece ^ (R / 8 % 8)), which is how the transposing
+// loader of the weight-gradient kernel keeps its scattered writes off each other's banks.
+template <class S, bool SWIZZLED, class Loader>
+__device__ __forceinline__ void contract(uint16_t* lds, unsigned steps, unsigned wm, unsigned wn, unsigned lane, Loader& loader,
+                                         f32x16 (&acc)[S::TM][S::TN])
+{
+    constexpr unsigned kBufA = S::kTileM * kRow, kBufB = S::kTileN * kRow;         // elements of one buffer
+    constexpr int kMfmas = S::TM * S::TN, kFrags = S::TM + S::TN;
+    static_assert(kStep == 64 && kFrags <= kMfmas, "four sub-steps; a fragment read after each of the first MFMAs");
+    uint16_t *a_cur = lds, *a_nxt = lds + kBufA, *b_cur = lds + 2 * kBufA, *b_nxt = lds + 2 * kBufA + kBufB;
+
+    // fragments: lane l reads row l % 32 of a 32-row tile, elements 16 kk + 8 (l / 32) .. + 7 of the step; in the
+    // order the MFMAs of a sub-step first need them: A 0, B 0 .. TN - 1, A 1 .. TM - 1
     const unsigned row = lane & 31u, half = lane >> 5;
-    auto fragment = [&](const uint16_t* tile, int i, int kk) {
-        const unsigned R = i * 32 + row;
+    bf16x8 fa[2][S::TM], fb[2][S::TN];
+    auto fragment = [&](auto set_c, auto f_c, const uint16_t* a_buf, const uint16_t* b_buf, unsigned kk) {
+        constexpr int set = decltype(set_c)::value, f = decltype(f_c)::value;
+        constexpr bool of_a = f == 0 || f > S::TN;
+        constexpr int index = f == 0 ? 0 : of_a ? f - S::TN : f - 1;
+        const unsigned R = (of_a ? wm : wn) + index * 32 + row;
         const unsigned piece = SWIZZLED ? ((kk * 2 + half) ^ ((R >> 3) & 7u)) : (kk * 2 + half);
-        return *reinterpret_cast<const bf16x8*>(tile + R * kRow + piece * 8u);
+        const bf16x8 v = *reinterpret_cast<const bf16x8*>((of_a ? a_buf : b_buf) + R * kRow + piece * 8u);
+        if constexpr (of_a) fa[set][index] = v;
+        else fb[set][index] = v;
     };
-#pragma unroll
-    for (int kk = 0; kk < kStep / 16; ++kk) {
-        bf16x8 a[TM], b[TN];
-#pragma unroll
-        for (int i = 0; i < TM; ++i) a[i] = fragment(a_tile, i, kk);
-#pragma unroll
-        for (int j = 0; j < TN; ++j) b[j] = fragment(b_tile, j, kk);
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+
+    loader.prologue(a_cur, b_cur);
+    __syncthreads();
+    static_for<0, kFrags>([&](auto f) { fragment(std::integral_constant<int, 0>{}, f, a_cur, b_cur, 0); });
+
+    unsigned s = 0;
+    auto substep = [&](auto kk_c) {
+        constexpr int KK = decltype(kk_c)::value, set = KK & 1;
+        using Next = std::integral_constant<int, set ^ 1>;
+        static_for<0, kMfmas>([&](auto i_c) {
+            constexpr int I = decltype(i_c)::value, i = I / S::TN, j = I % S::TN;
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][j], fa[set][i], acc[i][j], 0, 0, 0);
+            static_for<(I < kFrags ? I : kFrags), (I < kFrags ? I + 1 : kFrags)>([&](auto f) {
+                if constexpr (KK < 3) fragment(Next{}, f, a_cur, b_cur, KK + 1);
+                else fragment(Next{}, f, a_nxt, b_nxt, 0);          // the first ones of the next step
+            });
+            if constexpr (KK < 3) {
+                constexpr int kTasks = KK == 0 ? Loader::kTasks0 : KK == 1 ? Loader::kTasks1 : Loader::kTasks2;
+                static_for<share_begin<I, kMfmas, kTasks>, share_end<I, kMfmas, kTasks>>([&](auto t_c) {
+                    loader.template task<KK, decltype(t_c)::value>(a_nxt, b_nxt, s + 2);
+                });
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    };
+    for (; s < steps; ++s) {
+        substep(std::integral_constant<int, 0>{});
+        substep(std::integral_constant<int, 1>{});
+        substep(std::integral_constant<int, 2>{});
+        __syncthreads();
+        substep(std::integral_constant<int, 3>{});
+        uint16_t* x = a_cur; a_cur = a_nxt; a_nxt = x;
+        x = b_cur; b_cur = b_nxt; b_nxt = x;
     }
 }
+
+// Stores a wavefront's accumulators as bfloat16.  The MFMAs were given the column operand first, so tile (i, j)
+// holds, in register q of lane l, the output of row row0 + 32 i + l % 32 and column
+// col0 + 32 j + 8 (q / 4) + 4 (l / 32) + q % 4: a lane owns four neighbouring columns of one row.  Where the row
+// length is a multiple of 8 the wavefront's 32 TM x 32 TN block goes through LDS (`staging`, private to the
+// wavefront, rows of 32 TN + 8 elements) and leaves as 16-byte stores that cover whole 64 TN-byte row segments;
+// rows and columns outside the matrix are addressed past the buffer's extent, and the hardware drops them.
+// Otherwise single elements are stored.  addend: per column, binary32, in LDS, indexed from col0 (the bias), or nullptr.
+template <int TM, int TN>
+__device__ __forceinline__ void store_accumulators(const f32x16 (&acc)[TM][TN], uint16_t* out, unsigned rows, unsigned cols,
+                                                   unsigned row0, unsigned col0, unsigned lane, const float* addend,
+                                                   uint16_t* staging)
+{
+    constexpr unsigned kStride = 32 * TN + 8;                   // elements
+    const unsigned row = lane & 31u, col = 4u * (lane >> 5);
+    if (cols % 8u == 0) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const unsigned c = col + 32u * j + 8u * g;
+                f32x4 b = {0.0f, 0.0f, 0.0f, 0.0f};
+                if (addend) b = *reinterpret_cast<const f32x4*>(addend + c);
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+                    *reinterpret_cast<u32x2*>(staging + (row + 32u * i) * kStride + c) =
+                        u32x2{pack2(acc[i][j][4 * g] + b[0], acc[i][j][4 * g + 1] + b[1]),
+                              pack2(acc[i][j][4 * g + 2] + b[2], acc[i][j][4 * g + 3] + b[3])};
+            }
+        // the same wavefront reads back (LDS serves a wavefront's accesses in order): 4 TN lanes per row, 16 bytes each
+        constexpr unsigned kLanesPerRow = 4 * TN, kRowsPerPass = 64 / kLanesPerRow;
+        const __amdgpu_buffer_rsrc_t dst = whole_buffer(out, rows * cols * 2u);
+        const unsigned r_in = lane / kLanesPerRow, c_in = (lane % kLanesPerRow) * 8u;
+#pragma unroll
+        for (unsigned p = 0; p < 32u * TM / kRowsPerPass; ++p) {
+            const unsigned r = r_in + kRowsPerPass * p;
+            const u32x4 v = *reinterpret_cast<const u32x4*>(staging + r * kStride + c_in);
+            __builtin_amdgcn_raw_buffer_store_b128(
+                v, dst, (int)(row0 + r < rows && col0 + c_in < cols ? ((row0 + r) * cols + col0 + c_in) * 2u : kOutside), 0, 0);
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                const unsigned c = col + 32u * j + 8u * (q / 4) + (q % 4);
+                if (col0 + c >= cols) continue;
+                const float b = addend ? addend[c] : 0.0f;
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+                    if (row0 + row + 32u * i < rows)
+                        out[(size_t)(row0 + row + 32u * i) * cols + col0 + c] = (uint16_t)(pack2(acc[i][j][q] + b, 0.0f) & 0xFFFFu);
+            }
+    }
+}
+
+// Loader of the forward product.  Thread t moves the 16-byte piece t % 8 of rows t / 8, t / 8 + threads / 8, ...
+// of both operand tiles (8 threads: one 128-byte row of a step); a row outside the matrix is addressed past
+// the buffer's extent, where the hardware returns 0 and reads nothing.  The A pieces (the saved tensor) are
+// decoded word by word in the first two sub-steps, the B pieces (the weight) are copied in the third.
+template <int KIND, class S> struct LinearLoader {
+    static constexpr unsigned kRowsPerPass = S::kThreads / 8;
+    static constexpr unsigned kPassesA = S::kTileM / kRowsPerPass, kPassesB = S::kTileN / kRowsPerPass;
+    static_assert(kPassesA % 2 == 0, "the A pieces are staged in two halves");
+    static constexpr int kTasks0 = 4 * (kPassesA / 2), kTasks1 = kTasks0, kTasks2 = kPassesB;
+
+    __amdgpu_buffer_rsrc_t a_src, b_src;
+    unsigned a_off[kPassesA], b_off[kPassesB];      // byte offsets of this thread's pieces at step 0
+    unsigned wr;                                    // where this thread writes inside a buffer (elements)
+    unsigned steps;
+    u32x4 ra[kPassesA], rb[kPassesB];
+
+    __device__ __forceinline__ LinearLoader(const uint16_t* y_tagged, const uint16_t* w, unsigned M, unsigned N, unsigned K,
+                                            unsigned m0, unsigned n0, unsigned t)
+        : a_src(whole_buffer(y_tagged, M * K * 2u)), b_src(whole_buffer(w, N * K * 2u)), steps(K / kStep)
+    {
+        const unsigned r = t >> 3, piece = t & 7u;
+        wr = r * kRow + piece * 8u;
+#pragma unroll
+        for (unsigned p = 0; p < kPassesA; ++p)
+            a_off[p] = m0 + r + kRowsPerPass * p < M ? ((m0 + r + kRowsPerPass * p) * K + piece * 8u) * 2u : kOutside;
+#pragma unroll
+        for (unsigned p = 0; p < kPassesB; ++p)
+            b_off[p] = n0 + r + kRowsPerPass * p < N ? ((n0 + r + kRowsPerPass * p) * K + piece * 8u) * 2u : kOutside;
+    }
+    __device__ __forceinline__ unsigned step_bytes(unsigned step) const { return (step < steps ? step : steps - 1) * (kStep * 2u); }
+    __device__ __forceinline__ void load_a(unsigned p, unsigned step)
+    {
+        ra[p] = __builtin_amdgcn_raw_buffer_load_b128(a_src, (int)a_off[p], (int)step_bytes(step), 0);
+    }
+    __device__ __forceinline__ void load_b(unsigned p, unsigned step)
+    {
+        rb[p] = __builtin_amdgcn_raw_buffer_load_b128(b_src, (int)b_off[p], (int)step_bytes(step), 0);
+    }
+    __device__ __forceinline__ void prologue(uint16_t* a_buf, uint16_t* b_buf)
+    {
+#pragma unroll
+        for (unsigned p = 0; p < kPassesA; ++p) load_a(p, 0);
+#pragma unroll
+        for (unsigned p = 0; p < kPassesB; ++p) load_b(p, 0);
+#pragma unroll
+        for (unsigned p = 0; p < kPassesA; ++p) {
+            *reinterpret_cast<u32x4*>(a_buf + kRowsPerPass * p * kRow + wr) = decode8<KIND>(ra[p]);
+            load_a(p, 1);
+        }
+#pragma unroll
+        for (unsigned p = 0; p < kPassesB; ++p) {
+            *reinterpret_cast<u32x4*>(b_buf + kRowsPerPass * p * kRow + wr) = rb[p];
+            load_b(p, 1);
+        }
+    }
+    template <int KK, int T>
+    __device__ __forceinline__ void task(uint16_t* a_nxt, uint16_t* b_nxt, unsigned step)
+    {
+        if constexpr (KK < 2) {
+            constexpr int p = KK * (kPassesA / 2) + T / 4, word = T % 4;
+            ra[p][word] = decode2<KIND>(ra[p][word]);
+            if constexpr (word == 3) {
+                *reinterpret_cast<u32x4*>(a_nxt + kRowsPerPass * p * kRow + wr) = ra[p];
+                load_a(p, step);
+            }
+        } else {
+            *reinterpret_cast<u32x4*>(b_nxt + kRowsPerPass * T * kRow + wr) = rb[T];
+            load_b(T, step);
+        }
+    }
+};
 
 // out[M][N] = (|y_tagged| + C)[M][K] * w[N][K]^T (+ bias[N]); every matrix row-major, bfloat16; K a multiple of 64.
 template <int KIND, class S>
@@ -125,172 +321,157 @@ __global__ __launch_bounds__(S::kThreads) void sbit_linear_kernel(const uint16_t
                                                                   const uint16_t* bias, uint16_t* out,
                                                                   unsigned M, unsigned N, unsigned K)
 {
-    constexpr unsigned kRowsPerPass = S::kThreads / 8;          // 8 threads move one 128-byte operand row
-    constexpr unsigned kPassesA = S::kTileM / kRowsPerPass, kPassesB = S::kTileN / kRowsPerPass;
     extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
-    uint16_t* const a_lds = lds;                                   // [2][kTileM][kRow]
-    uint16_t* const b_lds = lds + 2 * S::kTileM * kRow;            // [2][kTileN][kRow]
-
     const unsigned n_tiles = (N + S::kTileN - 1) / S::kTileN;
     const unsigned tile = xcd_contiguous(blockIdx.x, gridDim.x);
     const unsigned m0 = (tile / n_tiles) * S::kTileM, n0 = (tile % n_tiles) * S::kTileN;   // neighbours share the rows of Y
-
     const unsigned t = threadIdx.x, lane = t & 63u, wave = t >> 6;
     const unsigned wm = (wave / S::WN) * (32 * S::TM), wn = (wave % S::WN) * (32 * S::TN);
 
-    // loader: thread t moves the 16-byte piece `piece` of rows r, r + kRowsPerPass, ... of both operand tiles
-    const unsigned r = t >> 3, piece = t & 7u;
-    const __amdgpu_buffer_rsrc_t a_src = whole_buffer(y_tagged, M * K * 2u), b_src = whole_buffer(w, N * K * 2u);
-    const unsigned a_off = ((m0 + r) * K + piece * 8u) * 2u, b_off = ((n0 + r) * K + piece * 8u) * 2u;
-    const unsigned lds_off = r * kRow + piece * 8u;
-
-    u32x4 ra[kPassesA], rb[kPassesB];
-    auto load = [&](unsigned k0) {
-        // a row outside the matrix is addressed past the buffer's extent: the hardware returns 0
-#pragma unroll
-        for (unsigned p = 0; p < kPassesA; ++p)
-            ra[p] = __builtin_amdgcn_raw_buffer_load_b128(
-                a_src, (int)(m0 + r + kRowsPerPass * p < M ? a_off + (kRowsPerPass * p * K + k0) * 2u : 0xFFFFFFF0u), 0, 0);
-#pragma unroll
-        for (unsigned p = 0; p < kPassesB; ++p)
-            rb[p] = __builtin_amdgcn_raw_buffer_load_b128(
-                b_src, (int)(n0 + r + kRowsPerPass * p < N ? b_off + (kRowsPerPass * p * K + k0) * 2u : 0xFFFFFFF0u), 0, 0);
-    };
-    auto stage = [&](unsigned buf) {
-#pragma unroll
-        for (unsigned p = 0; p < kPassesA; ++p)
-            *reinterpret_cast<u32x4*>(a_lds + buf * S::kTileM * kRow + kRowsPerPass * p * kRow + lds_off) = decode8<KIND>(ra[p]);
-#pragma unroll
-        for (unsigned p = 0; p < kPassesB; ++p)
-            *reinterpret_cast<u32x4*>(b_lds + buf * S::kTileN * kRow + kRowsPerPass * p * kRow + lds_off) = rb[p];
-    };
-
     f32x16 acc[S::TM][S::TN] = {};
-    const unsigned steps = K / kStep;
-    load(0);
-    stage(0);
+    LinearLoader<KIND, S> loader(y_tagged, w, M, N, K, m0, n0, t);
+    contract<S, false>(lds, K / kStep, wm, wn, lane, loader, acc);
+
+    // The operand buffers are free once every wavefront is here: each wavefront stages its block of the output in
+    // its own part of them; the tile's share of the bias sits behind, as binary32.
     __syncthreads();
-    for (unsigned s = 0; s < steps; ++s) {
-        const unsigned cur = s & 1u;
-        if (s + 1 < steps) load((s + 1) * kStep);
-        mfma_step<false, S::TM, S::TN>(a_lds + cur * S::kTileM * kRow + wm * kRow, b_lds + cur * S::kTileN * kRow + wn * kRow,
-                                       lane, acc);
-        if (s + 1 < steps) stage(cur ^ 1u);
+    float* const bias_lds = reinterpret_cast<float*>(lds + S::kOperandBytes / 2);
+    if (bias) {
+        for (unsigned c = t; c < (unsigned)S::kTileN; c += S::kThreads)
+            bias_lds[c] = n0 + c < N ? __uint_as_float((uint32_t)bias[n0 + c] << 16) : 0.0f;
         __syncthreads();
     }
-
-    // MFMA result layout: register q of lane l holds row 8 (q / 4) + 4 (l / 32) + q % 4, column l % 32
-#pragma unroll
-    for (int j = 0; j < S::TN; ++j) {
-        const unsigned col = n0 + wn + j * 32u + (lane & 31u);
-        if (col >= N) continue;
-        const float b = bias ? __uint_as_float((uint32_t)bias[col] << 16) : 0.0f;
-#pragma unroll
-        for (int i = 0; i < S::TM; ++i)
-#pragma unroll
-            for (int q = 0; q < 16; ++q) {
-                const unsigned row = m0 + wm + i * 32u + 8u * (q / 4) + 4u * (lane >> 5) + (q % 4);
-                if (row < M) out[(size_t)row * N + col] = (uint16_t)(pack2(acc[i][j][q] + b, 0.0f) & 0xFFFFu);
-            }
-    }
+    store_accumulators<S::TM, S::TN>(acc, out, M, N, m0 + wm, n0 + wn, lane, bias ? bias_lds + wn : nullptr,
+                                     lds + wave * (32 * S::TM) * (32 * S::TN + 8));
 }
 
+// Loader of the weight-gradient product.  The contraction index m is the slow one of both operands, so the
+// loader transposes: a thread takes the same 16-byte piece (8 consecutive n, or k) of two neighbouring rows
+// m, m + 1 and writes eight 32-bit words {row m in the low half, row m + 1 in the high half} into LDS rows
+// n .. n + 7 (k .. k + 7), whose 16-byte pieces are swizzled (see contract).  A wavefront takes 16 neighbouring
+// pieces of 4 neighbouring row pairs: its 64 scattered 32-bit LDS writes (one element index at a time) then
+// fall on all 32 banks twice over, which is as good as 256 bytes get.  A task is a quarter of such a pair of
+// pieces (two of the eight words); those of the saved tensor are decoded first.
+template <int KIND, class S> struct WgradLoader {
+    // per operand: 16-byte pieces per row, row pairs one pass of all threads covers, passes per step
+    static constexpr unsigned kPiecesG = S::kTileM / 8, kPairsG = S::kThreads / kPiecesG, kPassesG = kStep / (2 * kPairsG);
+    static constexpr unsigned kPiecesA = S::kTileN / 8, kPairsA = S::kThreads / kPiecesA, kPassesA = kStep / (2 * kPairsA);
+    static_assert(kPassesG * 2 * kPairsG == kStep && kPassesA * 2 * kPairsA == kStep, "a step is a whole number of passes");
+    static_assert(kPassesA % 2 == 0, "the pieces of the saved tensor are staged in two halves");
+    static constexpr int kTasks0 = 4 * (kPassesA / 2), kTasks1 = kTasks0, kTasks2 = 4 * kPassesG;
+
+    __amdgpu_buffer_rsrc_t g_src, a_src;
+    unsigned g_off[kPassesG][2], a_off[kPassesA][2];   // byte offsets of this thread's pieces at step 0
+    unsigned g_wr[kPassesG], a_wr[kPassesA];           // LDS element index of word 0 of each pair of pieces
+    unsigned g_step, a_step, steps;                    // bytes from one step to the next
+    u32x4 rg[kPassesG][2], ra[kPassesA][2];
+
+    // Word e of a pair of pieces goes to LDS row 8 piece + e at (swizzled) column mloc: e rows further down.
+    static __device__ __forceinline__ unsigned first_word(unsigned piece, unsigned mloc)
+    {
+        return piece * 8u * kRow + (((((mloc >> 3) ^ piece) & 7u) << 3) | (mloc & 7u));
+    }
+    __device__ __forceinline__ WgradLoader(const uint16_t* y_tagged, const uint16_t* grad_out, unsigned M, unsigned N, unsigned K,
+                                           unsigned n0, unsigned k0, unsigned t)
+        : g_src(whole_buffer(grad_out, M * N * 2u)), a_src(whole_buffer(y_tagged, M * K * 2u)),
+          g_step(kStep * N * 2u), a_step(kStep * K * 2u), steps(M / kStep)
+    {
+        const unsigned lane = t & 63u, wave = t >> 6;
+        const unsigned pair_g = (wave / (kPiecesG / 16)) * 4u + (lane >> 4), piece_g = (lane & 15u) + 16u * (wave % (kPiecesG / 16));
+        const unsigned pair_a = (wave / (kPiecesA / 16)) * 4u + (lane >> 4), piece_a = (lane & 15u) + 16u * (wave % (kPiecesA / 16));
+        const bool g_in = n0 + piece_g * 8u < N, a_in = k0 + piece_a * 8u < K;   // N and K are multiples of 8: a piece is in or out
+#pragma unroll
+        for (unsigned p = 0; p < kPassesG; ++p) {
+            const unsigned mloc = 2u * pair_g + 2u * kPairsG * p;
+            g_wr[p] = first_word(piece_g, mloc);
+#pragma unroll
+            for (unsigned h = 0; h < 2; ++h) g_off[p][h] = g_in ? ((mloc + h) * N + n0 + piece_g * 8u) * 2u : kOutside;
+        }
+#pragma unroll
+        for (unsigned p = 0; p < kPassesA; ++p) {
+            const unsigned mloc = 2u * pair_a + 2u * kPairsA * p;
+            a_wr[p] = first_word(piece_a, mloc);
+#pragma unroll
+            for (unsigned h = 0; h < 2; ++h) a_off[p][h] = a_in ? ((mloc + h) * K + k0 + piece_a * 8u) * 2u : kOutside;
+        }
+    }
+    __device__ __forceinline__ unsigned clamped(unsigned step) const { return step < steps ? step : steps - 1; }
+    __device__ __forceinline__ void load_g(unsigned p, unsigned step)
+    {
+#pragma unroll
+        for (unsigned h = 0; h < 2; ++h)
+            rg[p][h] = __builtin_amdgcn_raw_buffer_load_b128(g_src, (int)g_off[p][h], (int)(clamped(step) * g_step), 0);
+    }
+    __device__ __forceinline__ void load_a(unsigned p, unsigned step)
+    {
+#pragma unroll
+        for (unsigned h = 0; h < 2; ++h)
+            ra[p][h] = __builtin_amdgcn_raw_buffer_load_b128(a_src, (int)a_off[p][h], (int)(clamped(step) * a_step), 0);
+    }
+    // words 2 quarter and 2 quarter + 1 of a pair of pieces
+    static __device__ __forceinline__ void scatter(uint16_t* word0, const u32x4& lo, const u32x4& hi, int quarter)
+    {
+        *reinterpret_cast<uint32_t*>(word0 + (2 * quarter) * kRow) = __builtin_amdgcn_perm(hi[quarter], lo[quarter], 0x05040100u);
+        *reinterpret_cast<uint32_t*>(word0 + (2 * quarter + 1) * kRow) = __builtin_amdgcn_perm(hi[quarter], lo[quarter], 0x07060302u);
+    }
+    __device__ __forceinline__ void prologue(uint16_t* g_buf, uint16_t* a_buf)
+    {
+#pragma unroll
+        for (unsigned p = 0; p < kPassesG; ++p) load_g(p, 0);
+#pragma unroll
+        for (unsigned p = 0; p < kPassesA; ++p) load_a(p, 0);
+#pragma unroll
+        for (unsigned p = 0; p < kPassesG; ++p) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) scatter(g_buf + g_wr[p], rg[p][0], rg[p][1], q);
+            load_g(p, 1);
+        }
+#pragma unroll
+        for (unsigned p = 0; p < kPassesA; ++p) {
+            const u32x4 lo = decode8<KIND>(ra[p][0]), hi = decode8<KIND>(ra[p][1]);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) scatter(a_buf + a_wr[p], lo, hi, q);
+            load_a(p, 1);
+        }
+    }
+    template <int KK, int T>
+    __device__ __forceinline__ void task(uint16_t* g_nxt, uint16_t* a_nxt, unsigned step)
+    {
+        constexpr int quarter = T % 4;
+        if constexpr (KK < 2) {
+            constexpr int p = KK * (kPassesA / 2) + T / 4;
+            ra[p][0][quarter] = decode2<KIND>(ra[p][0][quarter]);
+            ra[p][1][quarter] = decode2<KIND>(ra[p][1][quarter]);
+            scatter(a_nxt + a_wr[p], ra[p][0], ra[p][1], quarter);
+            if constexpr (quarter == 3) load_a(p, step);
+        } else {
+            constexpr int p = T / 4;
+            scatter(g_nxt + g_wr[p], rg[p][0], rg[p][1], quarter);
+            if constexpr (quarter == 3) load_g(p, step);
+        }
+    }
+};
+
 // grad_w[N][K] = grad_out[M][N]^T * (|y_tagged| + C)[M][K]; every matrix row-major, bfloat16; M a multiple of 64,
-// N and K multiples of 8.  The contraction index m is the slow one of both operands, so the loader transposes:
-// a thread takes the same 16-byte piece (8 consecutive n, or k) of two neighbouring rows m, m + 1 and writes
-// eight 32-bit words {row m, row m + 1} into LDS rows n .. n + 7 (k .. k + 7), whose 16-byte pieces are
-// swizzled (see mfma_step).  From there on the kernel is the forward one: LDS rows are output rows / columns,
-// their elements the contraction.
+// N and K multiples of 8.  LDS rows are rows (n) and columns (k) of grad_w, their elements the contraction (m).
 template <int KIND, class S>
 __global__ __launch_bounds__(S::kThreads) void sbit_linear_wgrad_kernel(const uint16_t* y_tagged, const uint16_t* grad_out,
                                                                         uint16_t* grad_w, unsigned M, unsigned N, unsigned K)
 {
-    // per operand: 16-byte pieces per row, row pairs one pass of all threads covers, passes per step
-    constexpr unsigned kPiecesG = S::kTileM / 8, kPairsG = S::kThreads / kPiecesG, kPassesG = kStep / (2 * kPairsG);
-    constexpr unsigned kPiecesA = S::kTileN / 8, kPairsA = S::kThreads / kPiecesA, kPassesA = kStep / (2 * kPairsA);
-    static_assert(kPassesG * 2 * kPairsG == kStep && kPassesA * 2 * kPairsA == kStep, "a step is a whole number of passes");
     extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
-    uint16_t* const g_lds = lds;                                   // [2][kTileM (n)][kRow (m)]
-    uint16_t* const a_lds = lds + 2 * S::kTileM * kRow;            // [2][kTileN (k)][kRow (m)]
-
     const unsigned k_tiles = (K + S::kTileN - 1) / S::kTileN;
     const unsigned tile = xcd_contiguous(blockIdx.x, gridDim.x);
     const unsigned n0 = (tile / k_tiles) * S::kTileM, k0 = (tile % k_tiles) * S::kTileN;   // neighbours share the columns of dOut
-
     const unsigned t = threadIdx.x, lane = t & 63u, wave = t >> 6;
     const unsigned wm = (wave / S::WN) * (32 * S::TM), wn = (wave % S::WN) * (32 * S::TN);
 
-    // loader: thread t moves one piece (8 columns) of rows 2 pair, 2 pair + 1 (+ 2 kPairs, ...) of either operand tile.
-    // A wavefront takes 16 neighbouring pieces of 4 neighbouring row pairs: its 64 scattered 32-bit LDS writes
-    // (one element index e at a time) then fall on all 32 banks twice over, which is as good as 256 bytes get.
-    const unsigned pair_g = (wave / (kPiecesG / 16)) * 4u + (lane >> 4), piece_g = (lane & 15u) + 16u * (wave % (kPiecesG / 16));
-    const unsigned pair_a = (wave / (kPiecesA / 16)) * 4u + (lane >> 4), piece_a = (lane & 15u) + 16u * (wave % (kPiecesA / 16));
-    const __amdgpu_buffer_rsrc_t g_src = whole_buffer(grad_out, M * N * 2u), a_src = whole_buffer(y_tagged, M * K * 2u);
-    const bool g_in = n0 + piece_g * 8u < N, a_in = k0 + piece_a * 8u < K;  // N and K are multiples of 8: a piece is in or out
-    const unsigned g_off = (2u * pair_g * N + n0 + piece_g * 8u) * 2u, a_off = (2u * pair_a * K + k0 + piece_a * 8u) * 2u;
-
-    u32x4 rg[kPassesG][2], ra[kPassesA][2];
-    auto load = [&](unsigned m0) {
-#pragma unroll
-        for (unsigned p = 0; p < kPassesG; ++p)
-#pragma unroll
-            for (unsigned h = 0; h < 2; ++h)
-                rg[p][h] = __builtin_amdgcn_raw_buffer_load_b128(
-                    g_src, (int)(g_in ? g_off + (m0 + 2u * kPairsG * p + h) * N * 2u : 0xFFFFFFF0u), 0, 0);
-#pragma unroll
-        for (unsigned p = 0; p < kPassesA; ++p)
-#pragma unroll
-            for (unsigned h = 0; h < 2; ++h)
-                ra[p][h] = __builtin_amdgcn_raw_buffer_load_b128(
-                    a_src, (int)(a_in ? a_off + (m0 + 2u * kPairsA * p + h) * K * 2u : 0xFFFFFFF0u), 0, 0);
-    };
-    // Writes the 8 elements of both rows of a pair, as words {row m in the low half, row m + 1 in the high half},
-    // into LDS rows 8 piece .. 8 piece + 7 at (swizzled) column mloc.
-    auto scatter = [](uint16_t* tile, const u32x4& lo, const u32x4& hi, unsigned piece, unsigned mloc) {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const unsigned R = piece * 8u + e;
-            const unsigned col = ((((mloc >> 3) ^ (R >> 3)) & 7u) << 3) | (mloc & 7u);
-            *reinterpret_cast<uint32_t*>(tile + R * kRow + col) =
-                __builtin_amdgcn_perm(hi[e / 2], lo[e / 2], (e & 1) ? 0x07060302u : 0x05040100u);
-        }
-    };
-    auto stage = [&](unsigned buf) {
-#pragma unroll
-        for (unsigned p = 0; p < kPassesG; ++p)
-            scatter(g_lds + buf * S::kTileM * kRow, rg[p][0], rg[p][1], piece_g, 2u * pair_g + 2u * kPairsG * p);
-#pragma unroll
-        for (unsigned p = 0; p < kPassesA; ++p)
-            scatter(a_lds + buf * S::kTileN * kRow, decode8<KIND>(ra[p][0]), decode8<KIND>(ra[p][1]), piece_a,
-                    2u * pair_a + 2u * kPairsA * p);
-    };
-
     f32x16 acc[S::TM][S::TN] = {};
-    const unsigned steps = M / kStep;
-    load(0);
-    stage(0);
-    __syncthreads();
-    for (unsigned s = 0; s < steps; ++s) {
-        const unsigned cur = s & 1u;
-        if (s + 1 < steps) load((s + 1) * kStep);
-        mfma_step<true, S::TM, S::TN>(g_lds + cur * S::kTileM * kRow + wm * kRow, a_lds + cur * S::kTileN * kRow + wn * kRow,
-                                      lane, acc);
-        if (s + 1 < steps) stage(cur ^ 1u);
-        __syncthreads();
-    }
+    WgradLoader<KIND, S> loader(y_tagged, grad_out, M, N, K, n0, k0, t);
+    contract<S, true>(lds, M / kStep, wm, wn, lane, loader, acc);
 
-#pragma unroll
-    for (int j = 0; j < S::TN; ++j) {
-        const unsigned col = k0 + wn + j * 32u + (lane & 31u);
-        if (col >= K) continue;
-#pragma unroll
-        for (int i = 0; i < S::TM; ++i)
-#pragma unroll
-            for (int q = 0; q < 16; ++q) {
-                const unsigned row = n0 + wm + i * 32u + 8u * (q / 4) + 4u * (lane >> 5) + (q % 4);
-                if (row < N) grad_w[(size_t)row * K + col] = (uint16_t)(pack2(acc[i][j][q], 0.0f) & 0xFFFFu);
-            }
-    }
+    __syncthreads();       // the operand buffers are free once every wavefront is here: the output is staged there
+    store_accumulators<S::TM, S::TN>(acc, grad_w, N, K, n0 + wm, k0 + wn, lane, nullptr,
+                                     lds + wave * (32 * S::TM) * (32 * S::TN + 8));
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }

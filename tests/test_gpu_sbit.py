@@ -183,10 +183,22 @@ def product_errors(gpu, ref, abs_sum, terms):
 LINEAR_SHAPES = [(128, 128, 64), (256, 384, 192), (200, 136, 128), (72, 264, 320), (1, 8, 64), (130, 8, 64)]
 
 
+@pytest.fixture
+def tile(request):
+    """Forces one of the workgroup shapes of the two products (0: the library's own choice)."""
+    B.set_linear_tile(request.param)
+    yield request.param
+    B.set_linear_tile(0)
+
+
+TILES = pytest.mark.parametrize("tile", [0, 2, 4], indirect=True)
+
+
+@TILES
 @pytest.mark.parametrize("kind", KINDS)
-def test_linear_forward_decodes_while_it_loads(kind):
+def test_linear_forward_decodes_while_it_loads(kind, tile):
     for M, N, K in LINEAR_SHAPES:
-        PT.say(f"invact_sbit_linear_fwd {kind} M={M} N={N} K={K}")
+        PT.say(f"invact_sbit_linear_fwd {kind} M={M} N={N} K={K} tile={tile}")
         st, v = linear_inputs(kind, M, N, K, 900 + M)
         dev = {k: PT.to_device(a.reshape(-1), "bf16").view(a.shape) for k, a in st.items()}
         dec = O.sbit_decode(kind, "bf16", v["yt"].reshape(-1))[1].reshape(M, K)
@@ -205,10 +217,11 @@ def test_linear_forward_decodes_while_it_loads(kind):
         assert np.max(np.abs(got - two_step) / (2.0 * PT.ulp(two_step, "bf16") + (K + 2) * 2.0 ** -24 * abs_sum)) <= 1.0
 
 
+@TILES
 @pytest.mark.parametrize("kind", KINDS)
-def test_linear_weight_gradient_decodes_while_it_loads(kind):
+def test_linear_weight_gradient_decodes_while_it_loads(kind, tile):
     for M, N, K in [(64, 128, 128), (192, 384, 256), (128, 136, 200), (320, 72, 264), (64, 8, 8), (64, 8, 136)]:
-        PT.say(f"invact_sbit_linear_wgrad {kind} M={M} N={N} K={K}")
+        PT.say(f"invact_sbit_linear_wgrad {kind} M={M} N={N} K={K} tile={tile}")
         st, v = linear_inputs(kind, M, N, K, 950 + K)
         dev = {k: PT.to_device(a.reshape(-1), "bf16").view(a.shape) for k, a in st.items()}
         dec = O.sbit_decode(kind, "bf16", v["yt"].reshape(-1))[1].reshape(M, K)
@@ -220,11 +233,12 @@ def test_linear_weight_gradient_decodes_while_it_loads(kind):
         assert e.max() <= 1.0, (M, N, K, np.unravel_index(np.argmax(e), e.shape), e.max())
 
 
-def test_linear_at_a_transformer_block_size_on_sampled_outputs():
+@TILES
+def test_linear_at_a_transformer_block_size_on_sampled_outputs(tile):
     """4096 tokens of a 1024 -> 4096 -> 1024 block (the shape of the paper's MLP-block timing, a batch the oracle
     can follow): 2^14 sampled outputs of either product against the oracle's sums over their own rows and columns."""
     kind, M, N, K = "gelu_erf", 4096, 1024, 4096
-    PT.say(f"invact_sbit_linear fwd/wgrad {kind} M={M} N={N} K={K}, sampled")
+    PT.say(f"invact_sbit_linear fwd/wgrad {kind} M={M} N={N} K={K} tile={tile}, sampled")
     st, v = linear_inputs(kind, M, N, K, 77)
     dev = {k: PT.to_device(a.reshape(-1), "bf16").view(a.shape) for k, a in st.items()}
     dec = O.sbit_decode(kind, "bf16", v["yt"].reshape(-1))[1].reshape(M, K)
