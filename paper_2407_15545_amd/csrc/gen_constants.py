@@ -15,10 +15,13 @@ imported from or shared with it.
     binary32 loses nothing and needs one rounding fewer near y~ = 0).
   * A polynomial fit of erfcx(z) = exp(z^2) erfc(z) in w = 1 / (1 + p z), used
     by the erf form of GELU with bfloat16 storage:  erfcx(z) ~ w * sum_k a_k w^k on z in [0, 10];
-    for binary32 storage a table of degree-4 polynomials of erfcx(x / sqrt 2) / 2 on intervals of width 1/8.
+    for binary32 storage a table of degree-4 polynomials of erfcx(x / sqrt 2) / 2 on intervals of width 1/8
+    (two coefficients in binary64, three in binary32: 32 bytes a row).
   * A polynomial fit of 2^f on |f| <= 0.501 for the binary32-storage forward
     (the hardware exponential's 0.78 ulp would be the largest error there).
 """
+import struct
+
 import mpmath as mp
 import numpy as np
 import scipy.special as sp
@@ -62,10 +65,13 @@ def erfcx_fit(p, deg, zmax=10.0):
     return mono, err
 
 
-def mills_table(rows, per_unit, deg):
-    """G(x) = Phi(-x) exp(x^2 / 2) = erfcx(x / sqrt 2) / 2 on [0, rows / per_unit) as one polynomial per interval
-    of width 1 / per_unit: row i holds the monomial coefficients in t = per_unit x - i in [0, 1).
-    Returns (coefficients [rows][deg + 1], max relative error)."""
+def mills_table(rows, per_unit):
+    """G(x) = Phi(-x) exp(x^2 / 2) = erfcx(x / sqrt 2) / 2 on [0, rows / per_unit) as one degree-4 polynomial per
+    interval of width 1 / per_unit: row i holds the monomial coefficients in t = per_unit x - i in [0, 1), c0 and
+    c1 in binary64 and c2, c3, c4 in binary32 (their terms are below G / 64, so binary32 is enough for them: the
+    kernel evaluates c2 + t (c3 + t c4) in binary32 and the rest in binary64).
+    Returns (rows of (c0, c1, c2, c3, c4), max relative error of that mixed evaluation)."""
+    deg = 4
     G = lambda x: 0.5 * sp.erfcx(x / np.sqrt(2.0))
     k = np.arange(4 * deg + 8)
     node = np.cos(np.pi * (k + 0.5) / k.size)                  # Chebyshev nodes on [-1, 1]; t = (node + 1) / 2
@@ -76,9 +82,14 @@ def mills_table(rows, per_unit, deg):
         for ck in C.cheb2poly(cheb):                           # node = 2 t - 1
             mono = P.polyadd(mono, ck * pw)
             pw = P.polymul(pw, np.array([-1.0, 2.0]))
+        row = (float(mono[0]), float(mono[1]), f32(mono[2]), f32(mono[3]), f32(mono[4]))
         tt = np.linspace(0.0, 1.0, 4001)
-        worst = max(worst, np.abs(P.polyval(tt, mono) / G((i + tt) / per_unit) - 1).max())
-        table.append(mono)
+        t32 = tt.astype(np.float32)
+        q = (np.float32(row[4]) * t32 + np.float32(row[3])).astype(np.float32)
+        q = (q * t32 + np.float32(row[2])).astype(np.float32)
+        g = (q.astype(np.float64) * tt + row[1]) * tt + row[0]
+        worst = max(worst, np.abs(g / G((i + tt) / per_unit) - 1).max())
+        table.append(row)
     return table, worst
 
 
@@ -143,14 +154,20 @@ def main():
     out.append(arr("erfcx_fast", mono))
     # binary32 storage: erfcx from a table of short polynomials (held in LDS by the kernels): 116 intervals of
     # width 1/8 cover every |x| whose result is not yet +-0 or x itself in binary32
-    rows, per_unit, deg = 116, 8, 4
-    table, err = mills_table(rows, per_unit, deg)
-    out.append(f"// Phi(-x) exp(x^2/2) on [{0}, {rows / per_unit}): row i = coefficients in t = {per_unit} x - i of a degree-{deg} fit "
-               f"on [i/{per_unit}, (i+1)/{per_unit}); max rel. error {err:.2e}")
-    out.append(f"static constexpr int mills_rows = {rows}, mills_cols = {deg + 1}, mills_per_unit = {per_unit};")
+    rows, per_unit = 116, 8
+    table, err = mills_table(rows, per_unit)
+    out.append(f"// Phi(-x) exp(x^2/2) on [{0}, {rows / per_unit}): row i = coefficients in t = {per_unit} x - i of a degree-4 fit "
+               f"on [i/{per_unit}, (i+1)/{per_unit}); max rel. error {err:.2e}.")
+    out.append("// 32-bit words: for every row c0 and c1 as binary64 (low word first); then for every row c2, c3, c4 as binary32")
+    out.append("// and one word of padding (two arrays of 16-byte entries).")
+    out.append(f"static constexpr int mills_rows = {rows}, mills_per_unit = {per_unit};")
     out.append(f"#define INVACT_MILLS_TABLE \\")
     for i, row in enumerate(table):
-        out.append("    " + ", ".join(f"{v:.17g}" for v in row) + ("," if i + 1 < rows else "") + " \\")
+        words = struct.unpack("<4I", struct.pack("<dd", row[0], row[1]))
+        out.append("    " + ", ".join(f"0x{w:08x}u" for w in words) + ", \\")
+    for i, row in enumerate(table):
+        words = struct.unpack("<4I", struct.pack("<fffI", row[2], row[3], row[4], 0))
+        out.append("    " + ", ".join(f"0x{w:08x}u" for w in words) + ("," if i + 1 < rows else "") + " \\")
     out.append("")
     mono, err = exp2_fit(6)
     out.append(f"// 2^f ~ e0 + e1 f + ... on |f| <= 0.501; max rel. error {err:.2e}")

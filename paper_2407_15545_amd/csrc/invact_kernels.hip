@@ -435,7 +435,8 @@ struct GluFwdOp {                    // act = f(gate), s = [gate < T], h = f(gat
     }
     static constexpr int kMask = MASK_WRITE;
     static constexpr bool kMillsTable = KIND == GELU_ERF && S::kPrec == PRECISE   /* erfcx comes from the LDS table */;
-    static constexpr Shape kShape = pick<DT>({1, 16}, {1, 16});   // {tiles, resident cap}: binary32, bfloat16
+    // {tiles, resident cap}: binary32, bfloat16; the binary32 erf form has arithmetic enough to want every slot
+    static constexpr Shape kShape = pick<DT>({1, kMillsTable ? 32 : 16}, {1, 16});
 };
 
 template <int KIND, int DT>
@@ -610,24 +611,30 @@ struct SbitBwdOp {                   // s = sign bit of y_tagged; grad_x = grad_
 // Skeleton
 // ---------------------------------------------------------------------------
 
-// A workgroup is one wavefront.  PERSISTENT: the grid strides over the wave
-// tiles (a fixed number of workgroups per compute unit).  Otherwise every
-// workgroup handles kUnroll consecutive wave tiles and retires, and the
-// dispatcher balances the load.  The tile index comes from the workgroup index,
-// so every branch below is wave-uniform (the neighbour swap of the binary32
-// mask needs whole quads) and tile addresses stay in scalar registers.
+// A workgroup is one wavefront -- or four, for the operations that read the erfcx table: they share one copy
+// of it in LDS, which costs each of them a quarter of the copying.  PERSISTENT: the grid strides over the wave
+// tiles (a fixed number of workgroups per compute unit).  Otherwise every wavefront handles kUnroll consecutive
+// wave tiles and retires, and the dispatcher balances the load.  The tile index comes from the workgroup (and
+// wavefront) index, so every branch below is wave-uniform (the neighbour swap of the binary32 mask needs whole
+// quads) and tile addresses stay in scalar registers.
+template <class Op> constexpr int kGroupWaves = Op::kMillsTable ? 4 : 1;
+
 template <class Op, bool PERSISTENT>
-__global__ __launch_bounds__(kWave) void stream_kernel(const Op op, const size_t n)
+__global__ __launch_bounds__(kWave * kGroupWaves<Op>) void stream_kernel(const Op op, const size_t n)
 {
     constexpr int kUnroll = Op::kShape.unroll;
     constexpr size_t kWaveTile = Op::S::kWaveTile;
+    constexpr unsigned kWaves = kGroupWaves<Op>;
     const size_t wave_tiles = n / kWaveTile;
-    const unsigned lane = threadIdx.x;
-    if constexpr (Op::kMillsTable) fill_mills_table(lane);
+    const unsigned lane = threadIdx.x % kWave;
+    // which wavefront of the grid this is (uniform over the wavefront: make the compiler see it)
+    const size_t wave = kWaves == 1 ? (size_t)blockIdx.x
+                                    : (size_t)blockIdx.x * kWaves + __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    if constexpr (Op::kMillsTable) fill_mills_table(threadIdx.x, kWave * kWaves);
 
     if constexpr (PERSISTENT) {
-        const size_t stride = gridDim.x;
-        size_t t = blockIdx.x;
+        const size_t stride = (size_t)gridDim.x * kWaves;
+        size_t t = wave;
         for (; t + (kUnroll - 1) * stride < wave_tiles; t += kUnroll * stride) {
             typename Op::In in[kUnroll];
 #pragma unroll
@@ -641,7 +648,7 @@ __global__ __launch_bounds__(kWave) void stream_kernel(const Op op, const size_t
             op.run(in, t, lane);
         }
     } else {
-        const size_t t = (size_t)blockIdx.x * kUnroll;
+        const size_t t = wave * kUnroll;
         if (t + kUnroll <= wave_tiles) {
             typename Op::In in[kUnroll];
 #pragma unroll
@@ -662,7 +669,7 @@ __global__ __launch_bounds__(kWave) void stream_kernel(const Op op, const size_t
     // Tail: elements [kWaveTile wave_tiles, n), one per lane, by the first wavefront.
     // Whole 64-bit mask words are written (read), so the zero padding of the
     // last word comes from the ballot itself.
-    if (blockIdx.x == 0) {
+    if (wave == 0) {
         for (size_t base = wave_tiles * kWaveTile; base < n; base += 64) {
             const size_t i = base + lane;
             if constexpr (Op::kMask == MASK_WRITE) {
@@ -703,9 +710,9 @@ int cu_count()
 
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
-// Bytes of (unused) dynamic LDS that keep at most `resident` workgroups of a
-// kernel on one compute unit; the kernel is told once per device that it may
-// be launched with that much.
+// Bytes of (unused) dynamic LDS that keep at most `resident` wavefronts of a
+// kernel on one compute unit (whole workgroups, where a workgroup is several);
+// the kernel is told once per device that it may be launched with that much.
 template <class Op>
 unsigned occupancy_cap_lds(int resident)
 {
@@ -714,14 +721,14 @@ unsigned occupancy_cap_lds(int resident)
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
     if (!(prepared.load(std::memory_order_acquire) >> dev & 1)) {
+        // what the kernel declares itself (the erfcx table) counts against the same 160 KiB
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(stream_kernel<Op, false>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)kLdsPerCu) != hipSuccess) {
-            (void)hipGetLastError();
+                                (int)(kLdsPerCu - (Op::kMillsTable ? (unsigned)kMillsTableBytes : 0u))) != hipSuccess)
             return 0;
-        }
         prepared.fetch_or(uint64_t(1) << dev, std::memory_order_release);
     }
-    const unsigned share = kLdsPerCu / (unsigned)resident, own = Op::kMillsTable ? (unsigned)kMillsTableBytes : 0u;
+    const unsigned groups = (unsigned)resident / kGroupWaves<Op> ? (unsigned)resident / kGroupWaves<Op> : 1u;
+    const unsigned share = kLdsPerCu / groups, own = Op::kMillsTable ? (unsigned)kMillsTableBytes : 0u;
     return share > own ? share - own : 0;
 }
 
@@ -743,18 +750,19 @@ int launch(const Op& op, size_t n, hipStream_t stream)
     const size_t wave_tiles = n / Op::S::kWaveTile;
     const int per_cu = g_blocks_per_cu.load(std::memory_order_relaxed);
     if (per_cu == 0) {
-        size_t blocks = (wave_tiles + kUnroll - 1) / kUnroll;
+        constexpr size_t per_block = (size_t)kUnroll * kGroupWaves<Op>;
+        size_t blocks = (wave_tiles + per_block - 1) / per_block;
         if (blocks == 0) blocks = 1;                          // the tail still needs a wavefront
         if (blocks > 0x7FFFFFFFu) return INVACT_ERR_SIZE;
         const int forced = g_resident_override.load(std::memory_order_relaxed);
         const unsigned lds = occupancy_cap_lds<Op>(forced ? forced : Op::kShape.resident);
-        return enqueue(stream_kernel<Op, false>, (unsigned)blocks, kWave, lds, stream, op, n);
+        return enqueue(stream_kernel<Op, false>, (unsigned)blocks, kWave * kGroupWaves<Op>, lds, stream, op, n);
     } else {
-        size_t blocks = wave_tiles;
+        size_t blocks = (wave_tiles + kGroupWaves<Op> - 1) / kGroupWaves<Op>;
         const size_t cap = (size_t)cu_count() * (size_t)per_cu;
         if (blocks > cap) blocks = cap;
         if (blocks == 0) blocks = 1;
-        return enqueue(stream_kernel<Op, true>, (unsigned)blocks, kWave, 0, stream, op, n);
+        return enqueue(stream_kernel<Op, true>, (unsigned)blocks, kWave * kGroupWaves<Op>, 0, stream, op, n);
     }
 }
 

@@ -108,28 +108,31 @@ __device__ __forceinline__ float act_fast(float x)
 // 116 intervals of width 1/8 with a degree-4 polynomial each reach 3e-9.  The interval index and the position
 // inside it come from 8 |x| with one conversion and one v_fract_f32, both exact, and the five coefficients from
 // LDS: 10 slow-rate instructions less per element than the reciprocal-based fit (1 / (1 + p z) to 2^-30 needs a
-// Newton step in binary64, and its polynomial twice the degree).  Rows are 40 bytes apart, i.e. 10 banks: the
-// lanes of a wavefront read 16 neighbouring rows without a bank conflict.  Every wavefront copies the table
-// from global memory (4640 bytes, L2-resident) into its workgroup's LDS before its first element.
-__device__ const double g_mills_table[cst::mills_rows * cst::mills_cols] = { INVACT_MILLS_TABLE };
-constexpr int kMillsTableBytes = cst::mills_rows * cst::mills_cols * 8;
+// Newton step in binary64, and its polynomial twice the degree).  A row is two 128-bit reads: c0 and c1 in
+// binary64, and c2, c3, c4, whose terms are below G / 64, in binary32 (c2 + t (c3 + t c4) is evaluated in
+// binary32, at the full rate, the rest in binary64); LDS traffic is what this costs, so the row is kept short,
+// and its two halves live in two arrays of 16-byte entries: lanes that read different rows then spread over
+// all eight groups of four banks.
+// Every workgroup copies the table from global memory (3712 bytes, L2-resident) into its LDS before its first
+// element: a twentieth of the kernel's time with one wavefront per workgroup, which is why these kernels run four.
+__device__ __attribute__((aligned(16))) const uint32_t g_mills_table[cst::mills_rows * 8] = { INVACT_MILLS_TABLE };
+constexpr int kMillsTableBytes = cst::mills_rows * 32;
 constexpr float kMillsClamp = 14.49f;                      // 8 * 14.49 < mills_rows
 
-__device__ __forceinline__ double* mills_lds()
+typedef uint32_t mills_piece_t __attribute__((ext_vector_type(4)));      // (c0, c1) or (c2, c3, c4, -) of a row
+
+__device__ __forceinline__ mills_piece_t* mills_lds()
 {
-    __shared__ __attribute__((aligned(16))) double table[cst::mills_rows * cst::mills_cols];
+    __shared__ mills_piece_t table[cst::mills_rows * 2];
     return table;
 }
 
-// One wavefront (the whole workgroup) fills the LDS copy; `lane` = threadIdx.x < 64.
-__device__ __forceinline__ void fill_mills_table(unsigned lane)
+// The whole workgroup (`threads` of them, `thread` = threadIdx.x) fills the LDS copy.
+__device__ __forceinline__ void fill_mills_table(unsigned thread, unsigned threads)
 {
-    typedef double double2_t __attribute__((ext_vector_type(2)));
-    static_assert(cst::mills_rows * cst::mills_cols % 2 == 0, "copied in 16-byte pieces");
-    constexpr unsigned pieces = cst::mills_rows * cst::mills_cols / 2;
-    const double2_t* src = reinterpret_cast<const double2_t*>(g_mills_table);
-    double2_t* dst = reinterpret_cast<double2_t*>(mills_lds());
-    for (unsigned k = lane; k < pieces; k += 64) dst[k] = src[k];
+    const mills_piece_t* src = reinterpret_cast<const mills_piece_t*>(g_mills_table);
+    mills_piece_t* dst = mills_lds();
+    for (unsigned k = thread; k < cst::mills_rows * 2u; k += threads) dst[k] = src[k];
     __syncthreads();
 }
 
@@ -184,11 +187,13 @@ __device__ __forceinline__ Gate gate_precise(float x)
         out.xc = med3(x, -kMillsClamp, kMillsClamp);
         double xd = (double)out.xc;
         float m = fabsf(out.xc) * (float)cst::mills_per_unit;
-        const double* row = mills_lds() + __umul24((unsigned)m, cst::mills_cols);   // truncation: the interval
-        double t = (double)__builtin_amdgcn_fractf(m);                           // position inside it, exact
-        double g = row[cst::mills_cols - 1];
-#pragma unroll
-        for (int k = cst::mills_cols - 2; k >= 0; --k) g = fma(g, t, row[k]);
+        const mills_piece_t* row = mills_lds() + (unsigned)m;                       // truncation: the interval
+        const float tf = __builtin_amdgcn_fractf(m);                                // position inside it, exact
+        const mills_piece_t lo = row[0], hi = row[cst::mills_rows];
+        const float q = fmaf(fmaf(__uint_as_float(hi[2]), tf, __uint_as_float(hi[1])), tf, __uint_as_float(hi[0]));
+        const double t = (double)tf;
+        const double c0 = __hiloint2double((int)lo[1], (int)lo[0]), c1 = __hiloint2double((int)lo[3], (int)lo[2]);
+        double g = fma(fma((double)q, t, c1), t, c0);
         out.P = g * exp2_neg(xd * (-0.5 * kLog2eD), xd);
     }
     return out;
