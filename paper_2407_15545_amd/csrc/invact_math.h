@@ -199,13 +199,13 @@ __device__ __forceinline__ Gate gate_precise(float x)
     return out;
 }
 
-// f(x) = max(x, -0) - |x| P in binary64, one fused multiply-add: what the gated product and the sign-bit
-// variant start from.
+// f(x) - minus = (max(x, -0) - minus) - |x| P in binary64, one fused multiply-add: what the gated product
+// (minus = 0) and the sign-bit variant (minus = min f) start from.
 template <int KIND>
-__device__ __forceinline__ double act_precise(float x)
+__device__ __forceinline__ double act_precise(float x, double minus = 0.0)
 {
     Gate g = gate_precise<KIND>(x);
-    return fma(-fabs((double)g.xc), g.P, fmax((double)x, -0.0));
+    return fma(-fabs((double)g.xc), g.P, fmax((double)x, -0.0) - minus);
 }
 
 // The clamps above drop a NaN; put it back, as a quiet one: the precision-bit variant clears bit 0 of
@@ -248,9 +248,9 @@ __device__ __forceinline__ float act_minus_min_signed(float x)
         float d = act_fast<KIND>(x) - C;
         v = (d < 0.0f) ? 0.0f : d;                      // keeps a NaN
     } else {
-        double d = act_precise<KIND>(x) - (double)C;
-        v = (float)((d < 0.0) ? 0.0 : d);               // keeps a NaN
-        v = nan_through(x, v);
+        // max(x, -0) - C is exact in binary64 wherever it matters (for |x| > 2^28 the result rounds to x anyway),
+        // so f(x) - C still sees one rounding before the store; the clamp drops a NaN, which is put back
+        v = nan_through(x, (float)fmax(act_precise<KIND>(x, (double)C), 0.0));
     }
     return (x < KindConst<KIND>::T) ? -v : v;
 }
