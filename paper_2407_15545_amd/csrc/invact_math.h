@@ -189,10 +189,12 @@ __device__ __forceinline__ Gate gate_precise(float x)
         float m = fabsf(out.xc) * (float)cst::mills_per_unit;
         const mills_piece_t* row = mills_lds() + (unsigned)m;                       // truncation: the interval
         const float tf = __builtin_amdgcn_fractf(m);                                // position inside it, exact
-        const mills_piece_t lo = row[0], hi = row[cst::mills_rows];
-        const float q = fmaf(fmaf(__uint_as_float(hi[2]), tf, __uint_as_float(hi[1])), tf, __uint_as_float(hi[0]));
-        const double t = (double)tf;
-        const double c0 = __hiloint2double((int)lo[1], (int)lo[0]), c1 = __hiloint2double((int)lo[3], (int)lo[2]);
+        typedef double double2_t __attribute__((ext_vector_type(2)));
+        typedef float float4_t __attribute__((ext_vector_type(4)));
+        const double2_t lo = __builtin_bit_cast(double2_t, row[0]);                 // c0, c1
+        const float4_t hi = __builtin_bit_cast(float4_t, row[cst::mills_rows]);     // c2, c3, c4, -
+        const float q = fmaf(fmaf(hi[2], tf, hi[1]), tf, hi[0]);
+        const double t = (double)tf, c0 = lo[0], c1 = lo[1];
         double g = fma(fma((double)q, t, c1), t, c0);
         out.P = g * exp2_neg(xd * (-0.5 * kLog2eD), xd);
     }
