@@ -163,7 +163,7 @@ __device__ __forceinline__ double rcp_newton(double d)
 
 // The gate on the negative side in binary64: P = sigmoid(-|z|) or Phi(-|x|), and the clamped x it was computed
 // from (|x| is clamped where P is exactly 0 anyway, so that an infinite x meets that 0 as a finite factor).
-// The clamp drops a NaN and the callers put it back (nan_through).
+// The clamp drops a NaN; act_precise lets it through by its other operand.
 struct Gate { double P; float xc; };
 
 template <int KIND>
@@ -207,11 +207,14 @@ template <int KIND>
 __device__ __forceinline__ double act_precise(float x, double minus = 0.0)
 {
     Gate g = gate_precise<KIND>(x);
-    return fma(-fabs((double)g.xc), g.P, fmax((double)x, -0.0) - minus);
+    // max(x, -0) as a select, which lets a NaN x through where a maximum would drop it: the result is then a
+    // NaN, and a quiet one (the conversions quiet it), so that the precision-bit variant, which rewrites bit 0 of
+    // the stored pattern, cannot turn the signalling NaNs 0x7F800001 / 0xFF800001 into infinities
+    const float positive_part = (x < 0.0f) ? -0.0f : x;
+    return fma(-fabs((double)g.xc), g.P, (double)positive_part - minus);
 }
 
-// The clamps above drop a NaN; put it back, as a quiet one: the precision-bit variant clears bit 0 of
-// the stored pattern, which would turn the signalling NaNs 0x7F800001 / 0xFF800001 into infinities.
+// For the paths whose own clamp drops a NaN: put it back, as a quiet one.
 __device__ __forceinline__ float nan_through(float x, float v) { return (x != x) ? __uint_as_float(0x7FC00000u) : v; }
 
 // f(x) rounded once to binary32.
@@ -219,7 +222,7 @@ template <int KIND, int PREC>
 __device__ __forceinline__ float act(float x)
 {
     if constexpr (PREC == FAST) return act_fast<KIND>(x);
-    else return nan_through(x, (float)act_precise<KIND>(x));
+    else return (float)act_precise<KIND>(x);
 }
 
 // f(gate) and f(gate) * up, each rounded once (the product is formed from the
@@ -234,7 +237,6 @@ __device__ __forceinline__ void act_times(float gate, float up, float& a, float&
         double ad = act_precise<KIND>(gate);
         a = (float)ad;
         h = (float)(ad * (double)up);
-        a = nan_through(gate, a); h = nan_through(gate, h);
     }
 }
 
