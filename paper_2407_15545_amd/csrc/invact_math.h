@@ -313,8 +313,9 @@ __device__ __forceinline__ QParts q_parts(float y, bool left)
         // Eq. (6): 1 + (c0 + c1 sqrt(yt) + c2 yt) E, with yt = arg
         float E = cubic_exp2(cst::gelu_right_exp2, arg);
         if constexpr (PREC == FAST) {
-            float r = fmaf(R[2], arg, R[1] * sq);
-            out.qr    = fmaf(r, E, fmaf(R[0], E, 1.0f));
+            // 1 + (c0 + c1 sqrt(yt) + c2 yt) E as written: three operations; the rounding of the bracket is far
+            // below a bfloat16 ulp even where the sum passes through zero
+            out.qr    = fmaf(fmaf(R[2], arg, fmaf(R[1], sq, R[0])), E, 1.0f);
             out.small = 0.0f;                                   // not used
         } else {
             // the same sum with E multiplied in first: the partial sums stay below 1,
@@ -324,11 +325,21 @@ __device__ __forceinline__ QParts q_parts(float y, bool left)
             out.small = fmaf(R[1], sE, fmaf(c2y, E, R[0] * E));
         }
         // Eq. (5): c0 sqrt(y + c1) (2y + c2 sqrt(-y)) (|c3 y^2 + |c4 y + c5| + c6| + c7)
+        // The factor 2 of the middle bracket goes to c0 (exact: the results are the same bit for bit), which
+        // saves the doubling of y; with bfloat16 storage c0 goes on into the last bracket (its constants are
+        // rounded once more, which costs an ulp of binary32), which saves a product.
         float s2 = hw_sqrt(med3(-y, 0.0f, FLT_MAX));
-        float B  = fmaf(L[2], s2, y + y);
-        float inner = fabsf(fmaf(L[4], y, L[5]));
-        float outer = fabsf(fmaf(L[3], y * y, inner) + L[6]) + L[7];
-        out.ql = (L[0] * sq) * B * outer;
+        float B  = fmaf(0.5f * L[2], s2, y);
+        if constexpr (PREC == FAST) {
+            constexpr float k = 2.0f * L[0];                    // positive: it passes through both absolute values
+            float inner = fabsf(fmaf(k * L[4], y, k * L[5]));
+            float outer = fabsf(fmaf(k * L[3], y * y, inner) + k * L[6]) + k * L[7];
+            out.ql = sq * B * outer;
+        } else {
+            float inner = fabsf(fmaf(L[4], y, L[5]));
+            float outer = fabsf(fmaf(L[3], y * y, inner) + L[6]) + L[7];
+            out.ql = ((2.0f * L[0]) * sq) * B * outer;
+        }
     }
     return out;
 }
