@@ -111,7 +111,9 @@ class _SignBitActLinear(torch.autograd.Function):
     saved activation is f(x) - min f with the indicator in its sign bit.  In bfloat16, with shapes the fused
     products take (in_features a multiple of 64; for the weight gradient a token count that is a multiple of
     64 and out_features a multiple of 8), f(x) is rebuilt inside the two matrix products and never exists in
-    memory; otherwise invact_sbit_decode rebuilds it for a library GEMM and it is dropped again."""
+    memory; otherwise invact_sbit_decode rebuilds it for a library GEMM and it is dropped again.  The rebuilt
+    |Y| + C equals f(x) only to an absolute error of about one ulp at |C| (the stored f - C and the sum live on
+    the grid of max(|f|, |C|)): near x = 0 it keeps few of f(x)'s own digits, which in bfloat16 is visible."""
 
     @staticmethod
     def forward(ctx, x, weight, bias, kind):
