@@ -96,6 +96,18 @@ __device__ __forceinline__ unsigned xcd_contiguous(unsigned block, unsigned bloc
     return (blocks % 8u) ? block : (block % 8u) * (blocks / 8u) + block / 8u;
 }
 
+// Row and column of tile `tile` of a rows x cols grid of tiles, walked in bands of kBand rows, column by column
+// inside a band: the 32 tiles an XCD works on at a time then form a block of kBand x (32 / kBand) tiles and
+// share kBand + 32 / kBand operand panels, where a row-major walk would have them share 1 + 32.
+constexpr unsigned kBand = 4;      // 4 and 8 measure alike, 2 and 16 a few per cent lower
+struct TileAt { unsigned row, col; };
+__device__ __forceinline__ TileAt banded(unsigned tile, unsigned rows, unsigned cols)
+{
+    const unsigned band = tile / (kBand * cols), within = tile % (kBand * cols);
+    const unsigned height = rows - band * kBand < kBand ? rows - band * kBand : kBand;      // the last band may be lower
+    return TileAt{band * kBand + within % height, within / height};
+}
+
 // Compile-time loops: f(std::integral_constant<int, FIRST>) ... f(std::integral_constant<int, LAST - 1>).
 template <int FIRST, int... Is, class F>
 __device__ __forceinline__ void static_for_impl(std::integer_sequence<int, Is...>, F&& f)
@@ -323,8 +335,8 @@ __global__ __launch_bounds__(S::kThreads) void sbit_linear_kernel(const uint16_t
 {
     extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
     const unsigned n_tiles = (N + S::kTileN - 1) / S::kTileN;
-    const unsigned tile = xcd_contiguous(blockIdx.x, gridDim.x);
-    const unsigned m0 = (tile / n_tiles) * S::kTileM, n0 = (tile % n_tiles) * S::kTileN;   // neighbours share the rows of Y
+    const TileAt at = banded(xcd_contiguous(blockIdx.x, gridDim.x), gridDim.x / n_tiles, n_tiles);
+    const unsigned m0 = at.row * S::kTileM, n0 = at.col * S::kTileN;
     const unsigned t = threadIdx.x, lane = t & 63u, wave = t >> 6;
     const unsigned wm = (wave / S::WN) * (32 * S::TM), wn = (wave % S::WN) * (32 * S::TN);
 
@@ -460,8 +472,8 @@ __global__ __launch_bounds__(S::kThreads) void sbit_linear_wgrad_kernel(const ui
 {
     extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
     const unsigned k_tiles = (K + S::kTileN - 1) / S::kTileN;
-    const unsigned tile = xcd_contiguous(blockIdx.x, gridDim.x);
-    const unsigned n0 = (tile / k_tiles) * S::kTileM, k0 = (tile % k_tiles) * S::kTileN;   // neighbours share the columns of dOut
+    const TileAt at = banded(xcd_contiguous(blockIdx.x, gridDim.x), gridDim.x / k_tiles, k_tiles);
+    const unsigned n0 = at.row * S::kTileM, k0 = at.col * S::kTileN;
     const unsigned t = threadIdx.x, lane = t & 63u, wave = t >> 6;
     const unsigned wm = (wave / S::WN) * (32 * S::TM), wn = (wave % S::WN) * (32 * S::TN);
 
