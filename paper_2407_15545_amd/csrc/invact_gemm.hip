@@ -139,28 +139,49 @@ template <int I, int N, int COUNT> constexpr int share_end = (I + 1) * COUNT / N
 // first fragments of step s + 1.  The steps past the end of the contraction that the pipeline's tail asks for
 // are reloads of the last one and are never multiplied.
 //
-// SWIZZLED: the 16-byte pieces of LDS row R sit at position (piece ^ (R / 8 % 8)), which is how the transposing
-// loader of the weight-gradient kernel keeps its scattered writes off each other's banks.
-template <class S, bool SWIZZLED, class Loader>
+// Two LDS layouts.  Plain: [rows of the tile][kRow], the elements of a row one step of the contraction; a
+// fragment is one 128-bit read per lane (lane l: row l % 32, elements 16 kk + 8 (l / 32) .. + 7).  TRANSPOSED (the
+// weight gradient, whose operands have the contraction index as their slow one): [step of the contraction = 64
+// rows][rows of the tile + kPadT], as the tiles lie in memory; a fragment is two ds_read_b64_tr_b16 per lane.
+// That instruction transposes inside every group of 16 lanes: lane i of a group receives, as its element j, element
+// i % 4 of the 8 bytes lane i / 4 + 4 j of the group points at.  So lane r of a group points at contraction row
+// 4 t + r / 4 (t = 0, 1: the two reads), tile rows 4 (r % 4) .. + 3 of the group's 16, and lane i ends up with
+// contraction rows 4 t .. 4 t + 3 of its own tile row: the 8 consecutive ones an MFMA operand wants.
+constexpr unsigned kPadT = 16;          // elements: 4 contraction rows of 32 bytes each then fill all 32 banks once
+
+template <class S, bool TRANSPOSED, class Loader>
 __device__ __forceinline__ void contract(uint16_t* lds, unsigned steps, unsigned wm, unsigned wn, unsigned lane, Loader& loader,
                                          f32x16 (&acc)[S::TM][S::TN])
 {
-    constexpr unsigned kBufA = S::kTileM * kRow, kBufB = S::kTileN * kRow;         // elements of one buffer
+    constexpr unsigned kPitchA = S::kTileM + kPadT, kPitchB = S::kTileN + kPadT;   // TRANSPOSED: elements of an LDS row
+    constexpr unsigned kBufA = TRANSPOSED ? kStep * kPitchA : S::kTileM * kRow;    // elements of one buffer
+    constexpr unsigned kBufB = TRANSPOSED ? kStep * kPitchB : S::kTileN * kRow;
+    static_assert(2 * (kBufA + kBufB) * 2 <= S::kOperandBytes, "both layouts fit the operand buffers");
     constexpr int kMfmas = S::TM * S::TN, kFrags = S::TM + S::TN;
     static_assert(kStep == 64 && kFrags <= kMfmas, "four sub-steps; a fragment read after each of the first MFMAs");
     uint16_t *a_cur = lds, *a_nxt = lds + kBufA, *b_cur = lds + 2 * kBufA, *b_nxt = lds + 2 * kBufA + kBufB;
 
-    // fragments: lane l reads row l % 32 of a 32-row tile, elements 16 kk + 8 (l / 32) .. + 7 of the step; in the
-    // order the MFMAs of a sub-step first need them: A 0, B 0 .. TN - 1, A 1 .. TM - 1
+    // fragments, in the order the MFMAs of a sub-step first need them: A 0, B 0 .. TN - 1, A 1 .. TM - 1
     const unsigned row = lane & 31u, half = lane >> 5;
+    const unsigned tr_row = 8u * half + ((lane & 15u) >> 2), tr_col = 16u * ((lane >> 4) & 1u) + 4u * (lane & 3u);
     bf16x8 fa[2][S::TM], fb[2][S::TN];
     auto fragment = [&](auto set_c, auto f_c, const uint16_t* a_buf, const uint16_t* b_buf, unsigned kk) {
         constexpr int set = decltype(set_c)::value, f = decltype(f_c)::value;
         constexpr bool of_a = f == 0 || f > S::TN;
         constexpr int index = f == 0 ? 0 : of_a ? f - S::TN : f - 1;
-        const unsigned R = (of_a ? wm : wn) + index * 32 + row;
-        const unsigned piece = SWIZZLED ? ((kk * 2 + half) ^ ((R >> 3) & 7u)) : (kk * 2 + half);
-        const bf16x8 v = *reinterpret_cast<const bf16x8*>((of_a ? a_buf : b_buf) + R * kRow + piece * 8u);
+        bf16x8 v;
+        if constexpr (TRANSPOSED) {
+            typedef short short4_t __attribute__((ext_vector_type(4)));
+            typedef __attribute__((address_space(3))) short4_t lds_short4_t;
+            constexpr unsigned pitch = of_a ? kPitchA : kPitchB;
+            const uint16_t* at = (of_a ? a_buf : b_buf) + (16u * kk + tr_row) * pitch + (of_a ? wm : wn) + index * 32 + tr_col;
+            const short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_t*)at);
+            const short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_t*)(at + 4u * pitch));
+            v = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+        } else {
+            const unsigned R = (of_a ? wm : wn) + index * 32 + row;
+            v = *reinterpret_cast<const bf16x8*>((of_a ? a_buf : b_buf) + R * kRow + (kk * 2 + half) * 8u);
+        }
         if constexpr (of_a) fa[set][index] = v;
         else fb[set][index] = v;
     };
@@ -357,74 +378,49 @@ __global__ __launch_bounds__(S::kThreads) void sbit_linear_kernel(const uint16_t
                                      lds + wave * (32 * S::TM) * (32 * S::TN + 8));
 }
 
-// Loader of the weight-gradient product.  The contraction index m is the slow one of both operands, so the
-// loader transposes: a thread takes the same 16-byte piece (8 consecutive n, or k) of two neighbouring rows
-// m, m + 1 and writes eight 32-bit words {row m in the low half, row m + 1 in the high half} into LDS rows
-// n .. n + 7 (k .. k + 7), whose 16-byte pieces are swizzled (see contract).  A wavefront takes 16 neighbouring
-// pieces of 4 neighbouring row pairs: its 64 scattered 32-bit LDS writes (one element index at a time) then
-// fall on all 32 banks twice over, which is as good as 256 bytes get.  A task is a quarter of such a pair of
-// pieces (two of the eight words); those of the saved tensor are decoded first.
+// Loader of the weight-gradient product.  The contraction index m is the slow one of both operands, and their
+// tiles go into LDS as they lie in memory, [64 rows m][columns of the tile + kPadT]: the transposition happens
+// in the fragment reads (see contract).  Thread t moves the 16-byte piece t % pieces of rows t / pieces,
+// + threads / pieces, ... of either tile (pieces = columns of the tile / 8); N and K are multiples of 8, so a
+// piece is inside its matrix or outside, and one outside is addressed past the buffer's extent (zeros, which land
+// in rows or columns of the output that are never stored).  The pieces of the saved tensor are decoded word by
+// word in the first two sub-steps, those of dOut are copied in the third.
 template <int KIND, class S> struct WgradLoader {
-    // per operand: 16-byte pieces per row, row pairs one pass of all threads covers, passes per step
-    static constexpr unsigned kPiecesG = S::kTileM / 8, kPairsG = S::kThreads / kPiecesG, kPassesG = kStep / (2 * kPairsG);
-    static constexpr unsigned kPiecesA = S::kTileN / 8, kPairsA = S::kThreads / kPiecesA, kPassesA = kStep / (2 * kPairsA);
-    static_assert(kPassesG * 2 * kPairsG == kStep && kPassesA * 2 * kPairsA == kStep, "a step is a whole number of passes");
+    static constexpr unsigned kPiecesG = S::kTileM / 8, kRowsG = S::kThreads / kPiecesG, kPassesG = kStep / kRowsG;
+    static constexpr unsigned kPiecesA = S::kTileN / 8, kRowsA = S::kThreads / kPiecesA, kPassesA = kStep / kRowsA;
+    static_assert(kPassesG * kRowsG == kStep && kPassesA * kRowsA == kStep, "a step is a whole number of passes");
     static_assert(kPassesA % 2 == 0, "the pieces of the saved tensor are staged in two halves");
-    static constexpr int kTasks0 = 4 * (kPassesA / 2), kTasks1 = kTasks0, kTasks2 = 4 * kPassesG;
+    static constexpr unsigned kPitchG = S::kTileM + kPadT, kPitchA = S::kTileN + kPadT;
+    static constexpr int kTasks0 = 4 * (kPassesA / 2), kTasks1 = kTasks0, kTasks2 = kPassesG;
 
     __amdgpu_buffer_rsrc_t g_src, a_src;
-    unsigned g_off[kPassesG][2], a_off[kPassesA][2];   // byte offsets of this thread's pieces at step 0
-    unsigned g_wr[kPassesG], a_wr[kPassesA];           // LDS element index of word 0 of each pair of pieces
+    unsigned g_off[kPassesG], a_off[kPassesA];         // byte offsets of this thread's pieces at step 0
+    unsigned g_wr, a_wr;                               // where this thread writes inside a buffer (elements)
     unsigned g_step, a_step, steps;                    // bytes from one step to the next
-    u32x4 rg[kPassesG][2], ra[kPassesA][2];
+    u32x4 rg[kPassesG], ra[kPassesA];
 
-    // Word e of a pair of pieces goes to LDS row 8 piece + e at (swizzled) column mloc: e rows further down.
-    static __device__ __forceinline__ unsigned first_word(unsigned piece, unsigned mloc)
-    {
-        return piece * 8u * kRow + (((((mloc >> 3) ^ piece) & 7u) << 3) | (mloc & 7u));
-    }
     __device__ __forceinline__ WgradLoader(const uint16_t* y_tagged, const uint16_t* grad_out, unsigned M, unsigned N, unsigned K,
                                            unsigned n0, unsigned k0, unsigned t)
         : g_src(whole_buffer(grad_out, M * N * 2u)), a_src(whole_buffer(y_tagged, M * K * 2u)),
           g_step(kStep * N * 2u), a_step(kStep * K * 2u), steps(M / kStep)
     {
-        const unsigned lane = t & 63u, wave = t >> 6;
-        const unsigned pair_g = (wave / (kPiecesG / 16)) * 4u + (lane >> 4), piece_g = (lane & 15u) + 16u * (wave % (kPiecesG / 16));
-        const unsigned pair_a = (wave / (kPiecesA / 16)) * 4u + (lane >> 4), piece_a = (lane & 15u) + 16u * (wave % (kPiecesA / 16));
-        const bool g_in = n0 + piece_g * 8u < N, a_in = k0 + piece_a * 8u < K;   // N and K are multiples of 8: a piece is in or out
+        const unsigned row_g = t / kPiecesG, piece_g = t % kPiecesG, row_a = t / kPiecesA, piece_a = t % kPiecesA;
+        const bool g_in = n0 + piece_g * 8u < N, a_in = k0 + piece_a * 8u < K;
+        g_wr = row_g * kPitchG + piece_g * 8u;
+        a_wr = row_a * kPitchA + piece_a * 8u;
 #pragma unroll
-        for (unsigned p = 0; p < kPassesG; ++p) {
-            const unsigned mloc = 2u * pair_g + 2u * kPairsG * p;
-            g_wr[p] = first_word(piece_g, mloc);
+        for (unsigned p = 0; p < kPassesG; ++p) g_off[p] = g_in ? ((row_g + kRowsG * p) * N + n0 + piece_g * 8u) * 2u : kOutside;
 #pragma unroll
-            for (unsigned h = 0; h < 2; ++h) g_off[p][h] = g_in ? ((mloc + h) * N + n0 + piece_g * 8u) * 2u : kOutside;
-        }
-#pragma unroll
-        for (unsigned p = 0; p < kPassesA; ++p) {
-            const unsigned mloc = 2u * pair_a + 2u * kPairsA * p;
-            a_wr[p] = first_word(piece_a, mloc);
-#pragma unroll
-            for (unsigned h = 0; h < 2; ++h) a_off[p][h] = a_in ? ((mloc + h) * K + k0 + piece_a * 8u) * 2u : kOutside;
-        }
+        for (unsigned p = 0; p < kPassesA; ++p) a_off[p] = a_in ? ((row_a + kRowsA * p) * K + k0 + piece_a * 8u) * 2u : kOutside;
     }
     __device__ __forceinline__ unsigned clamped(unsigned step) const { return step < steps ? step : steps - 1; }
     __device__ __forceinline__ void load_g(unsigned p, unsigned step)
     {
-#pragma unroll
-        for (unsigned h = 0; h < 2; ++h)
-            rg[p][h] = __builtin_amdgcn_raw_buffer_load_b128(g_src, (int)g_off[p][h], (int)(clamped(step) * g_step), 0);
+        rg[p] = __builtin_amdgcn_raw_buffer_load_b128(g_src, (int)g_off[p], (int)(clamped(step) * g_step), 0);
     }
     __device__ __forceinline__ void load_a(unsigned p, unsigned step)
     {
-#pragma unroll
-        for (unsigned h = 0; h < 2; ++h)
-            ra[p][h] = __builtin_amdgcn_raw_buffer_load_b128(a_src, (int)a_off[p][h], (int)(clamped(step) * a_step), 0);
-    }
-    // words 2 quarter and 2 quarter + 1 of a pair of pieces
-    static __device__ __forceinline__ void scatter(uint16_t* word0, const u32x4& lo, const u32x4& hi, int quarter)
-    {
-        *reinterpret_cast<uint32_t*>(word0 + (2 * quarter) * kRow) = __builtin_amdgcn_perm(hi[quarter], lo[quarter], 0x05040100u);
-        *reinterpret_cast<uint32_t*>(word0 + (2 * quarter + 1) * kRow) = __builtin_amdgcn_perm(hi[quarter], lo[quarter], 0x07060302u);
+        ra[p] = __builtin_amdgcn_raw_buffer_load_b128(a_src, (int)a_off[p], (int)(clamped(step) * a_step), 0);
     }
     __device__ __forceinline__ void prologue(uint16_t* g_buf, uint16_t* a_buf)
     {
@@ -434,38 +430,34 @@ template <int KIND, class S> struct WgradLoader {
         for (unsigned p = 0; p < kPassesA; ++p) load_a(p, 0);
 #pragma unroll
         for (unsigned p = 0; p < kPassesG; ++p) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) scatter(g_buf + g_wr[p], rg[p][0], rg[p][1], q);
+            *reinterpret_cast<u32x4*>(g_buf + kRowsG * p * kPitchG + g_wr) = rg[p];
             load_g(p, 1);
         }
 #pragma unroll
         for (unsigned p = 0; p < kPassesA; ++p) {
-            const u32x4 lo = decode8<KIND>(ra[p][0]), hi = decode8<KIND>(ra[p][1]);
-#pragma unroll
-            for (int q = 0; q < 4; ++q) scatter(a_buf + a_wr[p], lo, hi, q);
+            *reinterpret_cast<u32x4*>(a_buf + kRowsA * p * kPitchA + a_wr) = decode8<KIND>(ra[p]);
             load_a(p, 1);
         }
     }
     template <int KK, int T>
     __device__ __forceinline__ void task(uint16_t* g_nxt, uint16_t* a_nxt, unsigned step)
     {
-        constexpr int quarter = T % 4;
         if constexpr (KK < 2) {
-            constexpr int p = KK * (kPassesA / 2) + T / 4;
-            ra[p][0][quarter] = decode2<KIND>(ra[p][0][quarter]);
-            ra[p][1][quarter] = decode2<KIND>(ra[p][1][quarter]);
-            scatter(a_nxt + a_wr[p], ra[p][0], ra[p][1], quarter);
-            if constexpr (quarter == 3) load_a(p, step);
+            constexpr int p = KK * (kPassesA / 2) + T / 4, word = T % 4;
+            ra[p][word] = decode2<KIND>(ra[p][word]);
+            if constexpr (word == 3) {
+                *reinterpret_cast<u32x4*>(a_nxt + kRowsA * p * kPitchA + a_wr) = ra[p];
+                load_a(p, step);
+            }
         } else {
-            constexpr int p = T / 4;
-            scatter(g_nxt + g_wr[p], rg[p][0], rg[p][1], quarter);
-            if constexpr (quarter == 3) load_g(p, step);
+            *reinterpret_cast<u32x4*>(g_nxt + kRowsG * T * kPitchG + g_wr) = rg[T];
+            load_g(T, step);
         }
     }
 };
 
 // grad_w[N][K] = grad_out[M][N]^T * (|y_tagged| + C)[M][K]; every matrix row-major, bfloat16; M a multiple of 64,
-// N and K multiples of 8.  LDS rows are rows (n) and columns (k) of grad_w, their elements the contraction (m).
+// N and K multiples of 8.  LDS rows are steps of the contraction (m), as in memory; the fragment reads transpose.
 template <int KIND, class S>
 __global__ __launch_bounds__(S::kThreads) void sbit_linear_wgrad_kernel(const uint16_t* y_tagged, const uint16_t* grad_out,
                                                                         uint16_t* grad_w, unsigned M, unsigned N, unsigned K)
