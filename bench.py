@@ -278,7 +278,7 @@ def main():
     sw.add_argument("--consumer", nargs="+", default=None, metavar="M,N,K",
                     help="time the sign-bit variant's fused products (forward and weight gradient) at these shapes "
                          "against invact_sbit_decode + torch's GEMM")
-    sw.add_argument("--linear-tile", type=int, nargs="+", default=[0], choices=[0, 2, 4],
+    sw.add_argument("--linear-tile", type=int, nargs="+", default=[0], choices=[0, 2, 3, 4],
                     help="with --consumer: force the fused products' workgroup tile (4: 256 x 256, 2: 128 x 128, 0: the library's choice)")
     args = ap.parse_args()
     if args.gpus != 1:

@@ -188,9 +188,10 @@ int invact_sbit_linear_wgrad(int kind, int dtype, const void* y_tagged, const vo
  */
 int invact_set_resident_blocks(int blocks);
 int invact_set_blocks_per_cu(int blocks_per_cu);
-/* The two invact_sbit_linear_* products choose their workgroup tile by the size of the output (256 x 256 where
- * that still gives every compute unit a workgroup, 128 x 128 otherwise): t = 4 or 2 forces the former or the
- * latter, 0 restores the choice.  Returns its argument, or a negative number if it is none of these. */
+/* The two invact_sbit_linear_* products choose their workgroup shape by the size of the output (a 256 x 256 tile
+ * where that still gives every compute unit a workgroup, 128 x 128 otherwise, with 8 wavefronts where a compute
+ * unit gets one such tile at most and 4 where it gets more): t = 4, 3 or 2 forces the first, second or third,
+ * 0 restores the choice.  Returns its argument, or a negative number if it is none of these. */
 int invact_set_linear_tile(int t);
 
 #ifdef __cplusplus

@@ -45,6 +45,7 @@ constexpr int kRow = kStep + 8;         // LDS row in elements: 144 bytes
 //          matters here because the activation operand pays for its decode on the way in.
 //   Small  128 x 128, 4 wavefronts of 64 x 64, two workgroups per compute unit: for outputs too small to give
 //          every compute unit a large tile.
+//   Small8 the same tile with 8 wavefronts of 64 x 32: for outputs that give a compute unit one such tile at most.
 template <int TM_, int TN_, int WM_, int WN_> struct Shape {
     static constexpr int TM = TM_, TN = TN_, WM = WM_, WN = WN_;
     static constexpr int kThreads = 64 * WM * WN;
@@ -56,6 +57,7 @@ template <int TM_, int TN_, int WM_, int WN_> struct Shape {
 };
 using Large = Shape<4, 2, 2, 4>;
 using Small = Shape<2, 2, 2, 2>;
+using Small8 = Shape<2, 1, 2, 4>;
 
 template <int KIND> constexpr float min_of_kind()
 {
@@ -158,7 +160,7 @@ __device__ __forceinline__ void contract(uint16_t* lds, unsigned steps, unsigned
     constexpr unsigned kBufB = TRANSPOSED ? kStep * kPitchB : S::kTileN * kRow;
     static_assert(2 * (kBufA + kBufB) * 2 <= S::kOperandBytes, "both layouts fit the operand buffers");
     constexpr int kMfmas = S::TM * S::TN, kFrags = S::TM + S::TN;
-    static_assert(kStep == 64 && kFrags <= kMfmas, "four sub-steps; a fragment read after each of the first MFMAs");
+    static_assert(kStep == 64, "four sub-steps");
     uint16_t *a_cur = lds, *a_nxt = lds + kBufA, *b_cur = lds + 2 * kBufA, *b_nxt = lds + 2 * kBufA + kBufB;
 
     // fragments, in the order the MFMAs of a sub-step first need them: A 0, B 0 .. TN - 1, A 1 .. TM - 1
@@ -197,7 +199,9 @@ __device__ __forceinline__ void contract(uint16_t* lds, unsigned steps, unsigned
         static_for<0, kMfmas>([&](auto i_c) {
             constexpr int I = decltype(i_c)::value, i = I / S::TN, j = I % S::TN;
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][j], fa[set][i], acc[i][j], 0, 0, 0);
-            static_for<(I < kFrags ? I : kFrags), (I < kFrags ? I + 1 : kFrags)>([&](auto f) {
+            // one after each of the first MFMAs (more where a sub-step has fewer MFMAs than fragments)
+            constexpr int kEach = (kFrags + kMfmas - 1) / kMfmas;
+            static_for<(I * kEach < kFrags ? I * kEach : kFrags), ((I + 1) * kEach < kFrags ? (I + 1) * kEach : kFrags)>([&](auto f) {
                 if constexpr (KK < 3) fragment(Next{}, f, a_cur, b_cur, KK + 1);
                 else fragment(Next{}, f, a_nxt, b_nxt, 0);          // the first ones of the next step
             });
@@ -504,29 +508,49 @@ template <class S> size_t tiles_of(size_t rows, size_t cols)
     return ((rows + S::kTileM - 1) / S::kTileM) * ((cols + S::kTileN - 1) / S::kTileN);
 }
 
-// The large tile where it still gives every compute unit a workgroup (256 of them), the small one otherwise.
-std::atomic<int> g_force_tile{0};                       // 0: choose; 2: small; 4: large (benchmarking)
-bool large_tile(size_t rows, size_t cols)
+// Which shape: the large tile where it still gives every compute unit a workgroup (256 of them); else 128 x 128,
+// with 8 wavefronts where there is at most one such workgroup per compute unit (two wavefronts per SIMD hide each
+// other's waits: +6 to +15 %), with 4 where there are more (several workgroups per compute unit do that already, and
+// the 4-wavefront shape reads a third less from LDS).
+std::atomic<int> g_force_tile{0};                       // 0: choose; 2: Small; 3: Small8; 4: Large (benchmarking, tests)
+enum class Tile { kLarge, kSmall, kSmall8 };
+Tile tile_for(size_t rows, size_t cols)
 {
-    const int forced = g_force_tile.load(std::memory_order_relaxed);
-    return forced ? forced == 4 : tiles_of<Large>(rows, cols) >= 256;
+    switch (g_force_tile.load(std::memory_order_relaxed)) {
+    case 2: return Tile::kSmall;
+    case 3: return Tile::kSmall8;
+    case 4: return Tile::kLarge;
+    default: break;
+    }
+    if (tiles_of<Large>(rows, cols) >= 256) return Tile::kLarge;
+    return tiles_of<Small>(rows, cols) <= 256 ? Tile::kSmall8 : Tile::kSmall;
 }
 
 template <int KIND>
 int run_linear(const uint16_t* a, const uint16_t* b, const uint16_t* c, uint16_t* o, unsigned m, unsigned n, unsigned k,
                hipStream_t stream)
 {
-    if (large_tile(m, n))
+    switch (tile_for(m, n)) {
+    case Tile::kLarge:
         return launch_tiles<sbit_linear_kernel<KIND, Large>, Large>(tiles_of<Large>(m, n), stream, a, b, c, o, m, n, k);
-    return launch_tiles<sbit_linear_kernel<KIND, Small>, Small>(tiles_of<Small>(m, n), stream, a, b, c, o, m, n, k);
+    case Tile::kSmall8:
+        return launch_tiles<sbit_linear_kernel<KIND, Small8>, Small8>(tiles_of<Small8>(m, n), stream, a, b, c, o, m, n, k);
+    default:
+        return launch_tiles<sbit_linear_kernel<KIND, Small>, Small>(tiles_of<Small>(m, n), stream, a, b, c, o, m, n, k);
+    }
 }
 
 template <int KIND>
 int run_wgrad(const uint16_t* a, const uint16_t* g, uint16_t* o, unsigned m, unsigned n, unsigned k, hipStream_t stream)
 {
-    if (large_tile(n, k))
+    switch (tile_for(n, k)) {
+    case Tile::kLarge:
         return launch_tiles<sbit_linear_wgrad_kernel<KIND, Large>, Large>(tiles_of<Large>(n, k), stream, a, g, o, m, n, k);
-    return launch_tiles<sbit_linear_wgrad_kernel<KIND, Small>, Small>(tiles_of<Small>(n, k), stream, a, g, o, m, n, k);
+    case Tile::kSmall8:
+        return launch_tiles<sbit_linear_wgrad_kernel<KIND, Small8>, Small8>(tiles_of<Small8>(n, k), stream, a, g, o, m, n, k);
+    default:
+        return launch_tiles<sbit_linear_wgrad_kernel<KIND, Small>, Small>(tiles_of<Small>(n, k), stream, a, g, o, m, n, k);
+    }
 }
 
 constexpr size_t kMaxElems = size_t(1) << 31;      // 32-bit byte offsets inside each bfloat16 matrix
@@ -580,11 +604,11 @@ extern "C" int invact_sbit_linear_wgrad(int kind, int dtype, const void* y_tagge
     }
 }
 
-// Benchmarking: 0 lets the library choose the tile of the two products above, 2 or 4 forces T (results are the
-// same up to the order of the binary32 sums).  Returns its argument, or -1 if it is none of these.
+// Benchmarking and tests: 0 lets the library choose the shape of the two products above, 2, 3 or 4 forces Small,
+// Small8 or Large (results are the same up to the order of the binary32 sums).  Returns its argument, or -1 if it is none of these.
 extern "C" int invact_set_linear_tile(int t)
 {
-    if (t != 0 && t != 2 && t != 4) return -1;
+    if (t != 0 && t != 2 && t != 3 && t != 4) return -1;
     g_force_tile.store(t, std::memory_order_relaxed);
     return t;
 }

@@ -193,7 +193,7 @@ def tile(request):
     B.set_linear_tile(0)
 
 
-TILES = pytest.mark.parametrize("tile", [0, 2, 4], indirect=True)
+TILES = pytest.mark.parametrize("tile", [0, 2, 3, 4], indirect=True)
 
 
 @TILES
