@@ -183,10 +183,11 @@ template <> struct Storage<INVACT_FP32, 4> : Binary32 {
         const uint32_t byte = ld8(tile_buffer(mask, t * kMaskBytes, kMaskBytes), lane >> 1);
         return (lane & 1) ? (byte >> 4) : (byte & 0xFu);
     }
-    static __device__ __forceinline__ void store_tagged(void* p, size_t t, unsigned lane, float (&v)[4], uint32_t m)
+    // ind[j] is the indicator of element j as 0.0f or 1.0f (indicator01)
+    static __device__ __forceinline__ void store_tagged(void* p, size_t t, unsigned lane, float (&v)[4], const float (&ind)[4])
     {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) v[j] = tag(v[j], (m >> j) & 1u);
+        for (int j = 0; j < 4; ++j) v[j] = tag(v[j], (uint32_t)ind[j]);
         store(p, t, lane, v);
     }
     static __device__ __forceinline__ uint32_t unpack_tagged(const Raw& r, float (&v)[4])
@@ -241,10 +242,10 @@ template <> struct Storage<INVACT_FP32, 8> : Binary32 {
         const uint32_t other = swap_with_neighbour(own);
         return (lane & 1) ? ((other >> 4) | (own & 0xF0u)) : ((own & 0xFu) | ((other & 0xFu) << 4));
     }
-    static __device__ __forceinline__ void store_tagged(void* p, size_t t, unsigned lane, float (&v)[8], uint32_t m)
+    static __device__ __forceinline__ void store_tagged(void* p, size_t t, unsigned lane, float (&v)[8], const float (&ind)[8])
     {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) v[j] = tag(v[j], (m >> j) & 1u);
+        for (int j = 0; j < 8; ++j) v[j] = tag(v[j], (uint32_t)ind[j]);
         store(p, t, lane, v);
     }
     static __device__ __forceinline__ uint32_t unpack_tagged(const Raw& r, float (&v)[8])
@@ -302,12 +303,13 @@ template <> struct Storage<INVACT_BF16, 8> {
         reinterpret_cast<uint16_t*>(p)[i] = (uint16_t)(pack2(v, 0.0f) & 0xFFFFu);
     }
     // precision-bit variant: bit 0 of each stored 16-bit pattern := bit j of m / read it back
-    static __device__ __forceinline__ void store_tagged(void* p, size_t t, unsigned lane, float (&v)[8], uint32_t m)
+    // (ind[j] is the indicator of element j as 0.0f or 1.0f: the two tag bits of a word are one exact binary32 sum)
+    static __device__ __forceinline__ void store_tagged(void* p, size_t t, unsigned lane, float (&v)[8], const float (&ind)[8])
     {
         u32x4 w;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const uint32_t bits = ((m >> (2 * j)) & 1u) | (((m >> (2 * j + 1)) & 1u) << 16);
+            const uint32_t bits = (uint32_t)fmaf(ind[2 * j + 1], 65536.0f, ind[2 * j]);
             w[j] = (pack2(v[2 * j], v[2 * j + 1]) & 0xFFFEFFFEu) | bits;
         }
         st128(tile_buffer(p, t * kTileBytes, kTileBytes), lane * 16, w);
@@ -333,14 +335,18 @@ template <> struct Storage<INVACT_BF16, 8> {
 // exactly 1.0 or 0.0 -- a fused multiply-add with the clamp modifier, which also turns a NaN into 0 and
 // -inf into 1 -- and sum_j 2^j [x_j < T] is exact in binary32.  Two full-rate instructions per element
 // instead of compare + select + or.
+template <int KIND>
+__device__ __forceinline__ float indicator01(float x)                  // [x < T] as 0.0f or 1.0f
+{
+    constexpr float kBig = 33554432.0f;                                // 2^25
+    return med3(fmaf(x, -kBig, KindConst<KIND>::T * kBig), 0.0f, 1.0f);
+}
 template <int KIND, int N>
 __device__ __forceinline__ uint32_t indicator_bits(const float (&v)[N])
 {
-    constexpr float kBig = 33554432.0f;                                // 2^25
-    float sum = med3(fmaf(v[0], -kBig, KindConst<KIND>::T * kBig), 0.0f, 1.0f);
+    float sum = indicator01<KIND>(v[0]);
 #pragma unroll
-    for (int j = 1; j < N; ++j)
-        sum = fmaf(med3(fmaf(v[j], -kBig, KindConst<KIND>::T * kBig), 0.0f, 1.0f), (float)(1u << j), sum);
+    for (int j = 1; j < N; ++j) sum = fmaf(indicator01<KIND>(v[j]), (float)(1u << j), sum);
     return (uint32_t)sum;
 }
 
@@ -482,11 +488,10 @@ struct PbitFwdOp {                   // y = f(x) with bit 0 := [x < T]
     __device__ __forceinline__ void load(In& in, size_t t, unsigned lane) const { in.x = S::load(x, t, lane); }
     __device__ __forceinline__ void run(const In& in, size_t t, unsigned lane) const
     {
-        float v[S::kElems]; S::unpack(in.x, v);
-        const uint32_t m = indicator_bits<KIND>(v);
+        float v[S::kElems], ind[S::kElems]; S::unpack(in.x, v);
 #pragma unroll
-        for (int j = 0; j < S::kElems; ++j) v[j] = act<KIND, S::kPrec>(v[j]);
-        S::store_tagged(y, t, lane, v, m);
+        for (int j = 0; j < S::kElems; ++j) { ind[j] = indicator01<KIND>(v[j]); v[j] = act<KIND, S::kPrec>(v[j]); }
+        S::store_tagged(y, t, lane, v, ind);
     }
     __device__ __forceinline__ bool scalar(size_t i, bool) const
     {
