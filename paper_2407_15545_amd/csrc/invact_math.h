@@ -137,8 +137,8 @@ __device__ __forceinline__ void fill_mills_table(unsigned thread, unsigned threa
 }
 
 // 2^(a b) for a binary64 product t = a b in [-30000, 0]:  t = n + f with n = round(t), |f| <= 1/2,
-// 2^f by a degree-6 polynomial in binary64 (relative error 2.6e-9: the hardware exponential's
-// 0.78 ulp of binary32 would be the largest error of the whole forward), and the scaling by 2^n
+// 2^f by a degree-6 polynomial (relative error 2.6e-9: the hardware exponential's 0.78 ulp of binary32
+// would be the largest error of the whole forward; its last two steps in binary64), and the scaling by 2^n
 // exact (v_ldexp_f64, no subnormal binary32 intermediate).  n comes from adding 1.5 * 2^52: the sum
 // is rounded to an integer, and since the low 32 bits of that constant's significand are zero the
 // low word of the sum is n itself in two's complement.  Both uses of the product are fused
@@ -148,9 +148,13 @@ __device__ __forceinline__ double exp2_neg(double a, double b)
     constexpr double kRound = 6755399441055744.0;        // 1.5 * 2^52
     double s = fma(a, b, kRound);
     double f = fma(a, b, kRound - s);                    // kRound - s = -n exactly
-    double p = cst::exp2_precise[6];
+    // the terms from f^2 on are below 0.07 of the result: binary32 is enough for them (a tenth of an ulp of the
+    // result), at the full rate and a fraction of the power of binary64
+    const float ff = (float)f;
+    float q = (float)cst::exp2_precise[6];
 #pragma unroll
-    for (int k = 5; k >= 0; --k) p = fma(p, f, cst::exp2_precise[k]);
+    for (int k = 5; k >= 2; --k) q = fmaf(q, ff, (float)cst::exp2_precise[k]);
+    const double p = fma(fma((double)q, f, cst::exp2_precise[1]), f, cst::exp2_precise[0]);
     return ldexp(p, __double2loint(s));
 }
 
