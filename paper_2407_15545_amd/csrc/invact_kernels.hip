@@ -27,7 +27,8 @@
 // the mask word being formed by a wave64 ballot there (and zero padding coming
 // for free).
 //
-// Launch shape.  A workgroup is ONE wavefront that handles kShape.unroll wave
+// Launch shape.  A workgroup is ONE wavefront (four for the kernels that read
+// the erfcx table from LDS: see stream_kernel) that handles kShape.unroll wave
 // tiles and retires; the hardware dispatcher balances the load.  HBM delivers
 // the most when a compute unit has roughly 32 to 96 KiB of loads in flight and
 // no more: beyond that the streams of too many wavefronts interleave in the
@@ -72,7 +73,7 @@ using namespace invact_dev;
 constexpr int kLoadAux = INVACT_LD_AUX, kStoreAux = INVACT_ST_AUX, kMaskAux = INVACT_MASK_AUX;
 constexpr int  kDefaultBlocksPerCu = INVACT_DEFAULT_BLOCKS_PER_CU;   // 0: one tile per workgroup
 constexpr int  kWaveSlotsPerCu = 32;              // resident wavefronts a compute unit can hold
-constexpr int  kWave = 64;                        // a workgroup is one wavefront
+constexpr int  kWave = 64;                        // lanes of a wavefront
 
 // Launch shape of an operation: wave tiles per wavefront and the cap on resident wavefronts per
 // compute unit (none if they would fill the kWaveSlotsPerCu slots anyway).
