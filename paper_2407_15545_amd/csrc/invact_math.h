@@ -218,8 +218,6 @@ __device__ __forceinline__ double act_precise(float x, double minus = 0.0)
     return fma(-fabs((double)g.xc), g.P, (double)positive_part - minus);
 }
 
-// For the paths whose own clamp drops a NaN: put it back, as a quiet one.
-__device__ __forceinline__ float nan_through(float x, float v) { return (x != x) ? __uint_as_float(0x7FC00000u) : v; }
 
 // f(x) rounded once to binary32.
 template <int KIND, int PREC>
@@ -257,8 +255,11 @@ __device__ __forceinline__ float act_minus_min_signed(float x)
         v = (d < 0.0f) ? 0.0f : d;                      // keeps a NaN
     } else {
         // max(x, -0) - C is exact in binary64 wherever it matters (for |x| > 2^28 the result rounds to x anyway),
-        // so f(x) - C still sees one rounding before the store; the clamp drops a NaN, which is put back
-        v = nan_through(x, (float)fmax(act_precise<KIND>(x, (double)C), 0.0));
+        // so f(x) - C still sees one rounding before the store.  The clamp comes after it, as a select that keeps
+        // a NaN; the difference is never a negative zero (the fused multiply-add rounds an exact, non-zero value
+        // of at least 2^-110, or gives +0), so a sign bit cannot survive it.
+        v = (float)act_precise<KIND>(x, (double)C);
+        v = (v < 0.0f) ? 0.0f : v;
     }
     return (x < KindConst<KIND>::T) ? -v : v;
 }
