@@ -153,8 +153,9 @@ int invact_sbit_bwd(int kind, int dtype, const void* y_tagged, const void* grad_
                     size_t n, hipStream_t stream);
 
 /*
- * Sign-bit variant, the consumer (Section 3.3 and its listing: "return (Y + C) @ W_linear" in
- * the forward, "dW = (Y + C)^T @ dOut" in the backward): matrix products that rebuild
+ * Sign-bit variant, the consumer (Section 3.3 and its listing, where the linear layer that
+ * follows the activation multiplies Y + C by its weight in the forward and forms its weight
+ * gradient from Y + C and dOut in the backward): matrix products that rebuild
  * |y_tagged| + C while they load the saved tensor, so that the activation itself is never
  * written to memory.  bfloat16 only (INVACT_ERR_DTYPE otherwise); products on the matrix
  * units with binary32 accumulation, |y_tagged| + C rounded to bfloat16 exactly as
@@ -163,9 +164,9 @@ int invact_sbit_bwd(int kind, int dtype, const void* y_tagged, const void* grad_
  *   invact_sbit_linear_wgrad:  grad_weight[n][k] = sum_m grad_out[m][n] * (|y_tagged[m][k]| + C)
  * y_tagged: in, M x K.  weight: in, N x K (the layout of a linear layer's weight).  bias: in,
  * N elements, or NULL.  out, grad_out: M x N.  grad_weight: out, N x K.  All row-major and
- * dense.  K must be a multiple of 64 for the forward, M a multiple of 64 for the weight
- * gradient, and every matrix must hold fewer than 2^31 elements (INVACT_ERR_SIZE otherwise;
- * M or N equal to 0 succeeds without a launch).  Matrix pointers must be 16-byte aligned.
+ * dense.  K must be a multiple of 64 for the forward; M a multiple of 64 and N and K multiples
+ * of 8 for the weight gradient; every matrix must hold fewer than 2^31 elements
+ * (INVACT_ERR_SIZE otherwise; an output with no elements succeeds without a launch).  Matrix pointers must be 16-byte aligned.
  * No aliasing between an output and an input.
  */
 int invact_sbit_linear_fwd(int kind, int dtype, const void* y_tagged, const void* weight, const void* bias,
