@@ -238,16 +238,26 @@ def consumer_timing(args):
                    lambda: torch.mm(g.t(), B.invact_sbit_decode(kind, yt.view(-1), y=tmp.view(-1)).view(M, K), out=gw),
                    lambda: torch.mm(g.t(), y, out=gw)),
         }
+        compared = set()                                       # the two comparisons are timed once per product
         for tile in args.linear_tile:
             B.set_linear_tile(tile)
-            for name, fns in cases.items():
-                ms = []
-                for fn in fns if tile == args.linear_tile[0] else fns[:1]:
-                    group_ms(torch, stream, fn, launches, 1)
-                    ms.append(group_ms(torch, stream, fn, launches, 5)[0])
-                cells = "  ".join(f"{t:>12.4f} {flops / t / 1e9:8.1f}" for t in ms)
-                print(f"{M:>8d} x {N:>5d} x {K:>5d}  {name:8s} {cells}" + (f"   [tile {tile}]" if tile else ""), flush=True)
+            for name, (fused, *others) in cases.items():
+                for splits in args.linear_splits if name == "dW" else [0]:
+                    B.set_linear_splits(splits)
+                    ws = B.sbit_linear_wgrad_workspace(M, N, K) if name == "dW" else 0
+                    workspace = torch.empty(ws, dtype=torch.uint8, device="cuda") if ws else None
+                    split = lambda: B.invact_sbit_linear_wgrad_ws(kind, yt, g, grad_weight=gw, workspace=workspace)
+                    ms = []
+                    for fn in [split if ws else fused] + ([] if name in compared else others):
+                        group_ms(torch, stream, fn, launches, 1)
+                        ms.append(group_ms(torch, stream, fn, launches, 5)[0])
+                    compared.add(name)
+                    cells = "  ".join(f"{t:>12.4f} {flops / t / 1e9:8.1f}" for t in ms)
+                    note = ", ".join(([f"tile {tile}"] if tile else []) + ([f"splits {splits}"] if splits else []) +
+                                     ([f"workspace {ws >> 20} MiB"] if ws else []))
+                    print(f"{M:>8d} x {N:>5d} x {K:>5d}  {name:8s} {cells}" + (f"   [{note}]" if note else ""), flush=True)
         B.set_linear_tile(0)
+        B.set_linear_splits(0)
 
 
 def main():
@@ -285,6 +295,9 @@ def main():
                          "against invact_sbit_decode + torch's GEMM")
     sw.add_argument("--linear-tile", type=int, nargs="+", default=[0], choices=[0, 2, 3, 4],
                     help="with --consumer: force the fused products' workgroup tile (4: 256 x 256, 2: 128 x 128, 0: the library's choice)")
+    sw.add_argument("--linear-splits", type=int, nargs="+", default=[0],
+                    help="with --consumer: force the number of parts the weight gradient's contraction is split into "
+                         "(0: the library's choice; 1: none)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: the path is element-wise and needs no exchange between GPUs, "

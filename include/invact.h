@@ -175,6 +175,25 @@ int invact_sbit_linear_wgrad(int kind, int dtype, const void* y_tagged, const vo
                              void* grad_weight, size_t M, size_t N, size_t K, hipStream_t stream);
 
 /*
+ * The same weight gradient, allowed to split its contraction (same passage: the sum over the batch of
+ * dOut^T (Y + C)).  A narrow layer has a small N x K output and a long sum over M: too few output tiles to
+ * occupy the chip.  This entry point then cuts the sum over M into parts, has each part's workgroups leave binary32
+ * partial sums in `workspace`, and adds them in a second kernel, always in the same order, so results are
+ * reproducible; they differ from invact_sbit_linear_wgrad's by the order of the binary32 additions only, and
+ * are the same bits where it does not split.
+ *   invact_sbit_linear_wgrad_workspace(M, N, K): bytes of workspace the shape needs; 0 where the product is not
+ *     split (then workspace may be NULL) or the shape is not one the product accepts.
+ *   workspace: device memory, 16-byte aligned, owned by the caller, at least that many bytes (workspace_bytes says
+ *     how many there are; INVACT_ERR_SIZE if too few).  Written and read by this call only: contents before and
+ *     after mean nothing, and calls that may run at the same time need a workspace each.
+ * Everything else as for invact_sbit_linear_wgrad.
+ */
+size_t invact_sbit_linear_wgrad_workspace(size_t M, size_t N, size_t K);
+int invact_sbit_linear_wgrad_ws(int kind, int dtype, const void* y_tagged, const void* grad_out,
+                                void* grad_weight, size_t M, size_t N, size_t K,
+                                void* workspace, size_t workspace_bytes, hipStream_t stream);
+
+/*
  * Launch tuning (process-wide, for benchmarking; results are bit-identical
  * whatever is set).  By default a workgroup is one wavefront that handles one
  * tile and retires, and every entry point caps the number of such workgroups
@@ -194,6 +213,11 @@ int invact_set_blocks_per_cu(int blocks_per_cu);
  * unit gets one such tile at most and 4 where it gets more): t = 4, 3 or 2 forces the first, second or third,
  * 0 restores the choice.  Returns its argument, or a negative number if it is none of these. */
 int invact_set_linear_tile(int t);
+/* invact_sbit_linear_wgrad_ws chooses by the shape into how many parts it splits the sum over M (none where the
+ * output has 256 tiles of 256 x 256 or more; else as many as give every compute unit a tile, each part at least 1024
+ * rows long): splits = 1..64 forces that number, capped at M / 64; 0 restores the choice.
+ * invact_sbit_linear_wgrad_workspace answers for the setting in force.  Returns its argument, or a negative number. */
+int invact_set_linear_splits(int splits);
 
 #ifdef __cplusplus
 }

@@ -36,6 +36,9 @@ _PROTOTYPES = {
     "invact_sbit_bwd": (_int, [_int, _int, _vp, _vp, _vp, _sz, _vp]),
     "invact_sbit_linear_fwd": (_int, [_int, _int, _vp, _vp, _vp, _vp, _sz, _sz, _sz, _vp]),
     "invact_sbit_linear_wgrad": (_int, [_int, _int, _vp, _vp, _vp, _sz, _sz, _sz, _vp]),
+    "invact_sbit_linear_wgrad_workspace": (_sz, [_sz, _sz, _sz]),
+    "invact_sbit_linear_wgrad_ws": (_int, [_int, _int, _vp, _vp, _vp, _sz, _sz, _sz, _vp, _sz, _vp]),
+    "invact_set_linear_splits": (_int, [_int]),
     "swiglu_invact_fwd": (_int, [_int, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "swiglu_invact_bwd": (_int, [_int, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
 }
@@ -250,9 +253,9 @@ def swiglu_invact_bwd(act, up, mask, grad_h, grad_gate=None, grad_up=None, strea
 
 
 def set_linear_tile(t):
-    """Tile of the fused sign-bit products: 4 (256 x 256), 2 (128 x 128) or 0 (chosen by the output's size)."""
+    """Tile of the fused sign-bit products: 4 (256 x 256), 3 or 2 (128 x 128 with 8 or 4 wavefronts), or 0 (chosen by the output's size)."""
     if lib().invact_set_linear_tile(int(t)) < 0:
-        raise ValueError("tile must be 0, 2 or 4")
+        raise ValueError("tile must be 0, 2, 3 or 4")
 
 
 def _matrices(*ts):
@@ -284,8 +287,18 @@ def invact_sbit_linear_fwd(kind, y_tagged, weight, bias=None, out=None, stream=N
     return out
 
 
-def invact_sbit_linear_wgrad(kind, y_tagged, grad_out, grad_weight=None, stream=None):
-    """grad_weight = grad_out^T (|y_tagged| + C): y_tagged [M, K], grad_out [M, N].  Returns grad_weight [N, K]."""
+def set_linear_splits(splits):
+    """Parts the contraction of invact_sbit_linear_wgrad_ws is split into: 1..64, or 0 (chosen by the shape)."""
+    if lib().invact_set_linear_splits(int(splits)) < 0:
+        raise ValueError("splits must be in 0..64")
+
+
+def sbit_linear_wgrad_workspace(M, N, K):
+    """Bytes of workspace invact_sbit_linear_wgrad_ws needs for this shape (0: it does not split the contraction)."""
+    return lib().invact_sbit_linear_wgrad_workspace(M, N, K)
+
+
+def _wgrad_args(y_tagged, grad_out, grad_weight):
     (M, K), (M2, N) = y_tagged.shape, grad_out.shape
     if M != M2:
         raise ValueError("y_tagged and grad_out must have the same number of rows")
@@ -294,7 +307,30 @@ def invact_sbit_linear_wgrad(kind, y_tagged, grad_out, grad_weight=None, stream=
     dt = _matrices(y_tagged, grad_out, grad_weight)
     if grad_weight.shape != (N, K):
         raise ValueError("grad_weight must be [N, K]")
+    return dt, M, N, K, grad_weight
+
+
+def invact_sbit_linear_wgrad(kind, y_tagged, grad_out, grad_weight=None, stream=None):
+    """grad_weight = grad_out^T (|y_tagged| + C): y_tagged [M, K], grad_out [M, N].  Returns grad_weight [N, K]."""
+    dt, M, N, K, grad_weight = _wgrad_args(y_tagged, grad_out, grad_weight)
     with _on_device(y_tagged.device):
         _check(lib().invact_sbit_linear_wgrad(_kind(kind), dt, y_tagged.data_ptr(), grad_out.data_ptr(),
                                               grad_weight.data_ptr(), M, N, K, _stream(stream)))
+    return grad_weight
+
+
+def invact_sbit_linear_wgrad_ws(kind, y_tagged, grad_out, grad_weight=None, workspace=None, stream=None):
+    """The same product, allowed to split its contraction through `workspace` (a contiguous uint8 tensor of at least
+    sbit_linear_wgrad_workspace(M, N, K) bytes on the same device; None: one is taken from torch's allocator)."""
+    dt, M, N, K, grad_weight = _wgrad_args(y_tagged, grad_out, grad_weight)
+    if workspace is None:
+        nbytes = sbit_linear_wgrad_workspace(M, N, K)
+        workspace = torch.empty(nbytes, dtype=torch.uint8, device=y_tagged.device) if nbytes else None
+    elif workspace.dtype != torch.uint8 or not workspace.is_contiguous() or workspace.device != y_tagged.device:
+        raise ValueError("workspace must be a contiguous uint8 tensor on the same device")
+    with _on_device(y_tagged.device):
+        _check(lib().invact_sbit_linear_wgrad_ws(_kind(kind), dt, y_tagged.data_ptr(), grad_out.data_ptr(),
+                                                 grad_weight.data_ptr(), M, N, K,
+                                                 None if workspace is None else workspace.data_ptr(),
+                                                 0 if workspace is None else workspace.numel(), _stream(stream)))
     return grad_weight

@@ -403,15 +403,17 @@ template <int KIND, class S> struct WgradLoader {
     unsigned g_step, a_step, steps;                    // bytes from one step to the next
     u32x4 rg[kPassesG], ra[kPassesA];
 
+    // first_step, steps: this workgroup's share of the contraction (rows 64 first_step .. 64 (first_step + steps) - 1 of M)
     __device__ __forceinline__ WgradLoader(const uint16_t* y_tagged, const uint16_t* grad_out, unsigned M, unsigned N, unsigned K,
-                                           unsigned n0, unsigned k0, unsigned t)
+                                           unsigned n0, unsigned k0, unsigned first_step, unsigned steps_, unsigned t)
         : g_src(whole_buffer(grad_out, M * N * 2u)), a_src(whole_buffer(y_tagged, M * K * 2u)),
-          g_step(kStep * N * 2u), a_step(kStep * K * 2u), steps(M / kStep)
+          g_step(kStep * N * 2u), a_step(kStep * K * 2u), steps(steps_)
     {
-        const unsigned row_g = t / kPiecesG, piece_g = t % kPiecesG, row_a = t / kPiecesA, piece_a = t % kPiecesA;
+        const unsigned row_g = first_step * kStep + t / kPiecesG, piece_g = t % kPiecesG;
+        const unsigned row_a = first_step * kStep + t / kPiecesA, piece_a = t % kPiecesA;
         const bool g_in = n0 + piece_g * 8u < N, a_in = k0 + piece_a * 8u < K;
-        g_wr = row_g * kPitchG + piece_g * 8u;
-        a_wr = row_a * kPitchA + piece_a * 8u;
+        g_wr = (t / kPiecesG) * kPitchG + piece_g * 8u;
+        a_wr = (t / kPiecesA) * kPitchA + piece_a * 8u;
 #pragma unroll
         for (unsigned p = 0; p < kPassesG; ++p) g_off[p] = g_in ? ((row_g + kRowsG * p) * N + n0 + piece_g * 8u) * 2u : kOutside;
 #pragma unroll
@@ -462,24 +464,85 @@ template <int KIND, class S> struct WgradLoader {
 
 // grad_w[N][K] = grad_out[M][N]^T * (|y_tagged| + C)[M][K]; every matrix row-major, bfloat16; M a multiple of 64,
 // N and K multiples of 8.  LDS rows are steps of the contraction (m), as in memory; the fragment reads transpose.
+//
+// The contraction can be split: the grid is `splits` x tiles workgroups, workgroup (split, tile) contracts over its
+// share of the M / 64 steps, and with splits > 1 it leaves its binary32 accumulators in `partial` instead of
+// storing the output: chunk split * tiles + tile, inside it wavefront by wavefront, 16-byte piece by piece in the
+// order of the accumulator registers, lane by lane (every store instruction then covers 1 KiB).  wgrad_sum_kernel adds the chunks of a
+// tile in the order of the splits and stores the output.  That is for outputs with too few tiles to fill the
+// chip and a long contraction (the weight gradient of a layer that is narrow on both sides).
+template <int TM, int TN>
+__device__ __forceinline__ size_t partial_at(size_t chunk, unsigned waves, unsigned wave, unsigned lane)
+{
+    return ((chunk * waves + wave) * (TM * TN * 4) * 64u + lane) * 4u;      // in floats; piece q adds 256 q
+}
+
 template <int KIND, class S>
 __global__ __launch_bounds__(S::kThreads) void sbit_linear_wgrad_kernel(const uint16_t* y_tagged, const uint16_t* grad_out,
-                                                                        uint16_t* grad_w, unsigned M, unsigned N, unsigned K)
+                                                                        uint16_t* grad_w, unsigned M, unsigned N, unsigned K,
+                                                                        unsigned splits, float* partial)
 {
     extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
-    const unsigned k_tiles = (K + S::kTileN - 1) / S::kTileN;
-    const TileAt at = banded(xcd_contiguous(blockIdx.x, gridDim.x), gridDim.x / k_tiles, k_tiles);
+    const unsigned k_tiles = (K + S::kTileN - 1) / S::kTileN, tiles = gridDim.x / splits;
+    const unsigned chunk = xcd_contiguous(blockIdx.x, gridDim.x), split = chunk / tiles;
+    const TileAt at = banded(chunk % tiles, tiles / k_tiles, k_tiles);
     const unsigned n0 = at.row * S::kTileM, k0 = at.col * S::kTileN;
     const unsigned t = threadIdx.x, lane = t & 63u, wave = t >> 6;
     const unsigned wm = (wave / S::WN) * (32 * S::TM), wn = (wave % S::WN) * (32 * S::TN);
+    // the M / 64 steps in `splits` shares that differ by one step at most
+    const unsigned all_steps = M / kStep, share = all_steps / splits, extra = all_steps % splits;
+    const unsigned first_step = split * share + (split < extra ? split : extra), steps = share + (split < extra ? 1u : 0u);
 
     f32x16 acc[S::TM][S::TN] = {};
-    WgradLoader<KIND, S> loader(y_tagged, grad_out, M, N, K, n0, k0, t);
-    contract<S, true>(lds, M / kStep, wm, wn, lane, loader, acc);
+    WgradLoader<KIND, S> loader(y_tagged, grad_out, M, N, K, n0, k0, first_step, steps, t);
+    contract<S, true>(lds, steps, wm, wn, lane, loader, acc);
 
+    if (splits > 1) {
+        float* const to = partial + partial_at<S::TM, S::TN>(chunk, S::WM * S::WN, wave, lane);
+#pragma unroll
+        for (int i = 0; i < S::TM; ++i)
+#pragma unroll
+            for (int j = 0; j < S::TN; ++j)
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+                    *reinterpret_cast<f32x4*>(to + ((i * S::TN + j) * 4 + g) * 256) =
+                        f32x4{acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+        return;
+    }
     __syncthreads();       // the operand buffers are free once every wavefront is here: the output is staged there
     store_accumulators<S::TM, S::TN>(acc, grad_w, N, K, n0 + wm, k0 + wn, lane, nullptr,
                                      lds + wave * (32 * S::TM) * (32 * S::TN + 8));
+}
+
+// Second pass of a split weight gradient: one wavefront per wavefront of the first pass (workgroup tile * waves +
+// wave) adds that wavefront's accumulators over the splits, first split first, and stores them as the first
+// pass would have.
+template <class S>
+__global__ __launch_bounds__(64) void wgrad_sum_kernel(const float* partial, uint16_t* grad_w, unsigned N, unsigned K,
+                                                       unsigned tiles, unsigned splits)
+{
+    __shared__ __attribute__((aligned(16))) uint16_t staging[(32 * S::TM) * (32 * S::TN + 8)];
+    constexpr unsigned kWaves = S::WM * S::WN;
+    const unsigned k_tiles = (K + S::kTileN - 1) / S::kTileN;
+    const unsigned tile = blockIdx.x / kWaves, wave = blockIdx.x % kWaves, lane = threadIdx.x;
+    const TileAt at = banded(tile, tiles / k_tiles, k_tiles);
+    const unsigned wm = (wave / S::WN) * (32 * S::TM), wn = (wave % S::WN) * (32 * S::TN);
+
+    f32x16 acc[S::TM][S::TN] = {};
+    for (unsigned split = 0; split < splits; ++split) {
+        const float* const from = partial + partial_at<S::TM, S::TN>((size_t)split * tiles + tile, kWaves, wave, lane);
+#pragma unroll
+        for (int i = 0; i < S::TM; ++i)
+#pragma unroll
+            for (int j = 0; j < S::TN; ++j)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const f32x4 v = *reinterpret_cast<const f32x4*>(from + ((i * S::TN + j) * 4 + g) * 256);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[i][j][4 * g + e] += v[e];
+                }
+    }
+    store_accumulators<S::TM, S::TN>(acc, grad_w, N, K, at.row * S::kTileM + wm, at.col * S::kTileN + wn, lane, nullptr, staging);
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -540,16 +603,65 @@ int run_linear(const uint16_t* a, const uint16_t* b, const uint16_t* c, uint16_t
     }
 }
 
-template <int KIND>
-int run_wgrad(const uint16_t* a, const uint16_t* g, uint16_t* o, unsigned m, unsigned n, unsigned k, hipStream_t stream)
+// How a weight gradient with an N x K output and M / 64 steps of contraction runs: tile shape, number of splits of
+// the contraction, and the bytes of binary32 partial sums that needs (0 when it is not split).
+std::atomic<int> g_force_splits{0};                     // 0: choose; 1 .. kMaxSplits: force (benchmarking, tests)
+constexpr unsigned kMaxSplits = 64;
+struct WgradPlan { Tile tile; unsigned splits; size_t tiles, bytes; };
+WgradPlan plan_wgrad(size_t M, size_t N, size_t K, bool may_split)
 {
-    switch (tile_for(n, k)) {
-    case Tile::kLarge:
-        return launch_tiles<sbit_linear_wgrad_kernel<KIND, Large>, Large>(tiles_of<Large>(n, k), stream, a, g, o, m, n, k);
-    case Tile::kSmall8:
-        return launch_tiles<sbit_linear_wgrad_kernel<KIND, Small8>, Small8>(tiles_of<Small8>(n, k), stream, a, g, o, m, n, k);
-    default:
-        return launch_tiles<sbit_linear_wgrad_kernel<KIND, Small>, Small>(tiles_of<Small>(n, k), stream, a, g, o, m, n, k);
+    WgradPlan plan{tile_for(N, K), 1, 0, 0};
+    const size_t steps = M / kStep;
+    const int forced = g_force_splits.load(std::memory_order_relaxed);
+    if (may_split && forced > 0) {
+        plan.splits = (unsigned)(forced < (int)steps ? forced : steps);
+    } else if (may_split && g_force_tile.load(std::memory_order_relaxed) == 0) {
+        // Fewer large tiles than compute units (256).  Split so that every compute unit gets one, as long as a part
+        // stays kMinSteps long (each part costs a write and a read of 4 bytes per output element); if not even
+        // half of them would get a large tile that way, do the same with the small tile.
+        constexpr size_t kMinSteps = 16;
+        const size_t large = tiles_of<Large>(N, K), small = tiles_of<Small>(N, K), most = steps / kMinSteps;
+        if (large < 256) {
+            size_t splits = 256 / large < most ? 256 / large : most;
+            if (splits > 1 && large * splits >= 128) {
+                plan.tile = Tile::kLarge;
+            } else {
+                splits = small < 256 ? (256 / small < most ? 256 / small : most) : 1;
+                if (splits > 1) plan.tile = Tile::kSmall8;
+            }
+            if (splits > 1) plan.splits = (unsigned)(splits < kMaxSplits ? splits : kMaxSplits);
+        }
+    }
+    size_t tile_elems;
+    switch (plan.tile) {
+    case Tile::kLarge:  plan.tiles = tiles_of<Large>(N, K), tile_elems = Large::kTileM * Large::kTileN; break;
+    case Tile::kSmall8: plan.tiles = tiles_of<Small8>(N, K), tile_elems = Small8::kTileM * Small8::kTileN; break;
+    default:            plan.tiles = tiles_of<Small>(N, K), tile_elems = Small::kTileM * Small::kTileN; break;
+    }
+    plan.bytes = plan.splits > 1 ? plan.splits * plan.tiles * tile_elems * sizeof(float) : 0;
+    return plan;
+}
+
+template <int KIND, class S>
+int run_wgrad_shape(const WgradPlan& plan, const uint16_t* a, const uint16_t* g, uint16_t* o, unsigned m, unsigned n, unsigned k,
+                    float* partial, hipStream_t stream)
+{
+    const unsigned tiles = (unsigned)plan.tiles, splits = plan.splits;
+    if (int e = launch_tiles<sbit_linear_wgrad_kernel<KIND, S>, S>(plan.tiles * splits, stream, a, g, o, m, n, k, splits, partial))
+        return e;
+    if (splits == 1) return INVACT_OK;
+    wgrad_sum_kernel<S><<<dim3(tiles * S::WM * S::WN), dim3(64), 0, stream>>>(partial, o, n, k, tiles, splits);
+    return hipGetLastError() == hipSuccess ? INVACT_OK : INVACT_ERR_HIP;
+}
+
+template <int KIND>
+int run_wgrad(const WgradPlan& plan, const uint16_t* a, const uint16_t* g, uint16_t* o, unsigned m, unsigned n, unsigned k,
+              float* partial, hipStream_t stream)
+{
+    switch (plan.tile) {
+    case Tile::kLarge:  return run_wgrad_shape<KIND, Large>(plan, a, g, o, m, n, k, partial, stream);
+    case Tile::kSmall8: return run_wgrad_shape<KIND, Small8>(plan, a, g, o, m, n, k, partial, stream);
+    default:            return run_wgrad_shape<KIND, Small>(plan, a, g, o, m, n, k, partial, stream);
     }
 }
 
@@ -585,23 +697,50 @@ extern "C" int invact_sbit_linear_fwd(int kind, int dtype, const void* y_tagged,
     }
 }
 
-extern "C" int invact_sbit_linear_wgrad(int kind, int dtype, const void* y_tagged, const void* grad_out,
-                                        void* grad_weight, size_t M, size_t N, size_t K, hipStream_t stream)
+namespace {
+
+int wgrad_entry(int kind, int dtype, const void* y_tagged, const void* grad_out, void* grad_weight, size_t M, size_t N, size_t K,
+                bool may_split, void* workspace, size_t workspace_bytes, hipStream_t stream)
 {
     if (int e = check_kind_dtype(kind, dtype)) return e;
     if (M == 0 || M % kStep != 0 || N % 8 != 0 || K % 8 != 0 || !fits(M, K) || !fits(N, K) || !fits(M, N))
         return INVACT_ERR_SIZE;
     if (N == 0 || K == 0) return INVACT_OK;
-    if (!y_tagged || !grad_out || !grad_weight) return INVACT_ERR_NULL;
-    if (!aligned16(y_tagged) || !aligned16(grad_out) || !aligned16(grad_weight)) return INVACT_ERR_ALIGN;
+    const WgradPlan plan = plan_wgrad(M, N, K, may_split);
+    if (plan.bytes > workspace_bytes || plan.tiles * plan.splits > 0x7FFFFFFFu / 8u /* wavefronts of the summing pass */) return INVACT_ERR_SIZE;
+    if (!y_tagged || !grad_out || !grad_weight || (plan.bytes && !workspace)) return INVACT_ERR_NULL;
+    if (!aligned16(y_tagged) || !aligned16(grad_out) || !aligned16(grad_weight) || (plan.bytes && !aligned16(workspace)))
+        return INVACT_ERR_ALIGN;
     const uint16_t *a = static_cast<const uint16_t*>(y_tagged), *g = static_cast<const uint16_t*>(grad_out);
     uint16_t* o = static_cast<uint16_t*>(grad_weight);
+    float* const partial = static_cast<float*>(workspace);
     const unsigned m = (unsigned)M, n = (unsigned)N, k = (unsigned)K;
     switch (kind) {
-    case INVACT_GELU_TANH: return run_wgrad<INVACT_GELU_TANH>(a, g, o, m, n, k, stream);
-    case INVACT_GELU_ERF:  return run_wgrad<INVACT_GELU_ERF>(a, g, o, m, n, k, stream);
-    default:               return run_wgrad<INVACT_SILU>(a, g, o, m, n, k, stream);
+    case INVACT_GELU_TANH: return run_wgrad<INVACT_GELU_TANH>(plan, a, g, o, m, n, k, partial, stream);
+    case INVACT_GELU_ERF:  return run_wgrad<INVACT_GELU_ERF>(plan, a, g, o, m, n, k, partial, stream);
+    default:               return run_wgrad<INVACT_SILU>(plan, a, g, o, m, n, k, partial, stream);
     }
+}
+
+}  // namespace
+
+extern "C" int invact_sbit_linear_wgrad(int kind, int dtype, const void* y_tagged, const void* grad_out,
+                                        void* grad_weight, size_t M, size_t N, size_t K, hipStream_t stream)
+{
+    return wgrad_entry(kind, dtype, y_tagged, grad_out, grad_weight, M, N, K, false, nullptr, 0, stream);
+}
+
+extern "C" size_t invact_sbit_linear_wgrad_workspace(size_t M, size_t N, size_t K)
+{
+    if (M == 0 || M % kStep != 0 || N % 8 != 0 || K % 8 != 0 || N == 0 || K == 0 || !fits(N, K)) return 0;
+    return plan_wgrad(M, N, K, true).bytes;
+}
+
+extern "C" int invact_sbit_linear_wgrad_ws(int kind, int dtype, const void* y_tagged, const void* grad_out,
+                                           void* grad_weight, size_t M, size_t N, size_t K, void* workspace,
+                                           size_t workspace_bytes, hipStream_t stream)
+{
+    return wgrad_entry(kind, dtype, y_tagged, grad_out, grad_weight, M, N, K, true, workspace, workspace_bytes, stream);
 }
 
 // Benchmarking and tests: 0 lets the library choose the shape of the two products above, 2, 3 or 4 forces Small,
@@ -611,4 +750,13 @@ extern "C" int invact_set_linear_tile(int t)
     if (t != 0 && t != 2 && t != 3 && t != 4) return -1;
     g_force_tile.store(t, std::memory_order_relaxed);
     return t;
+}
+
+// Benchmarking and tests: 0 lets invact_sbit_linear_wgrad_ws choose into how many parts it splits the contraction,
+// 1 .. 64 forces that number (capped at the number of 64-row steps).  Returns its argument, or -1 if it is out of range.
+extern "C" int invact_set_linear_splits(int splits)
+{
+    if (splits < 0 || splits > (int)kMaxSplits) return -1;
+    g_force_splits.store(splits, std::memory_order_relaxed);
+    return splits;
 }

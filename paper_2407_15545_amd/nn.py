@@ -136,7 +136,9 @@ class _SignBitActLinear(torch.autograd.Function):
         N = weight.shape[0]
         g2 = _dense(grad_out.reshape(-1, N))
         if y_tagged.dtype == torch.bfloat16 and g2.dtype == torch.bfloat16 and M % 64 == 0 and N % 8 == 0 and K % 8 == 0 and M > 0:
-            grad_w = B.invact_sbit_linear_wgrad(ctx.kind, y_tagged, g2).to(weight.dtype)
+            # a narrow layer's weight gradient splits its long sum over the tokens; the workspace for the partial
+            # sums comes from torch's allocator and goes back to it
+            grad_w = B.invact_sbit_linear_wgrad_ws(ctx.kind, y_tagged, g2).to(weight.dtype)
         else:
             grad_w = g2.t().mm(B.invact_sbit_decode(ctx.kind, y_tagged.view(-1)).view(M, K))
         grad_b = g2.sum(0) if ctx.has_bias else None

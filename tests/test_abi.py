@@ -88,6 +88,18 @@ def test_argument_validation_happens_before_any_launch():
     assert wg(1, 1, a16, None, a16, 128, 128, 64, None) == ERR_NULL
     assert wg(1, 1, a16, a16, odd, 128, 128, 64, None) == ERR_ALIGN
     assert wg(1, 1, a16, a16, a16, 128, 0, 64, None) == OK
+    # the weight gradient that may split its contraction: what it asks for, and what it refuses (host logic only)
+    ws, need = lib.invact_sbit_linear_wgrad_ws, lib.invact_sbit_linear_wgrad_workspace
+    assert need(8192, 4096, 4096) == 0                           # 256 tiles of 256 x 256: not split
+    assert need(8192, 1024, 4096) == 4 * 64 * 256 * 256 * 4      # 64 tiles: four parts of binary32 partial tiles
+    assert need(2048, 1024, 4096) == 2 * 64 * 256 * 256 * 4      # parts of at least 16 steps
+    assert need(64, 128, 128) == 0 and need(100, 128, 64) == 0 and need(0, 8, 8) == 0
+    assert ws(1, 1, a16, a16, a16, 8192, 1024, 4096, a16, (1 << 26) - 16, None) == ERR_SIZE
+    assert ws(1, 1, a16, a16, a16, 8192, 1024, 4096, None, 1 << 26, None) == ERR_NULL
+    assert ws(1, 1, a16, a16, a16, 8192, 1024, 4096, a8, 1 << 26, None) == ERR_ALIGN
+    assert ws(1, 1, a16, a16, a16, 100, 128, 64, a16, 1 << 26, None) == ERR_SIZE
+    assert ws(1, 0, a16, a16, a16, 8192, 1024, 4096, a16, 1 << 26, None) == ERR_DTYPE
+    assert ws(1, 1, a16, a16, a16, 8192, 0, 4096, None, 0, None) == OK
     # n == 0 is a successful no-op, whatever the pointers
     assert fwd(0, 0, None, None, None, 0, None) == OK
     assert bwd(2, 1, None, None, None, None, 0, None) == OK

@@ -235,6 +235,68 @@ def test_linear_weight_gradient_decodes_while_it_loads(kind, tile):
         assert e.max() <= 1.0, (M, N, K, np.unravel_index(np.argmax(e), e.shape), e.max())
 
 
+@pytest.fixture
+def splits(request):
+    """Forces the number of parts invact_sbit_linear_wgrad_ws splits its contraction into (0: the library's choice)."""
+    B.set_linear_splits(request.param)
+    yield request.param
+    B.set_linear_splits(0)
+
+
+@TILES
+@pytest.mark.parametrize("splits", [0, 1, 2, 3, 5, 64], indirect=True)
+def test_linear_weight_gradient_with_a_split_contraction(tile, splits):
+    """The entry point that may split the contraction over M through a workspace: against the oracle at every
+    number of parts (320 rows are 5 steps: shares of 3 + 2, 2 + 2 + 1, 1 each, and more parts than steps), and
+    bit for bit against the plain entry point where it does not split."""
+    kind = "gelu_tanh"
+    for M, N, K in [(320, 136, 200), (192, 384, 256), (64, 8, 8), (1024, 72, 264)]:
+        PT.say(f"invact_sbit_linear_wgrad_ws {kind} M={M} N={N} K={K} tile={tile} splits={splits}")
+        st, v = linear_inputs(kind, M, N, K, 990 + K)
+        dev = {k: PT.to_device(a.reshape(-1), "bf16").view(a.shape) for k, a in st.items()}
+        dec = O.sbit_decode(kind, "bf16", v["yt"].reshape(-1))[1].reshape(M, K)
+        ref = O.sbit_linear_wgrad(kind, "bf16", v["yt"], v["g"])
+        nbytes = B.sbit_linear_wgrad_workspace(M, N, K)
+        assert (nbytes > 0) == (min(splits, M // 64) > 1), (nbytes, splits)       # the library's own choice: none at these sizes
+        workspace = torch.full((nbytes + 64,), 0xFF, dtype=torch.uint8, device="cuda")     # NaNs wherever it is not written
+        gw = B.invact_sbit_linear_wgrad_ws(kind, dev["yt"], dev["g"], workspace=workspace[:nbytes] if nbytes else None)
+        torch.cuda.synchronize()
+        assert bool((workspace[nbytes:] == 0xFF).all()), "wrote past the workspace it asked for"
+        got = PT.to_f64(gw.reshape(-1)).reshape(N, K)
+        e = product_errors(got, ref, np.abs(v["g"]).T @ np.abs(dec), M)
+        assert e.max() <= 1.0, (M, N, K, np.unravel_index(np.argmax(e), e.shape), e.max())
+        if nbytes == 0:
+            assert torch.equal(gw, B.invact_sbit_linear_wgrad(kind, dev["yt"], dev["g"]))
+        else:
+            with pytest.raises(B.InvactError) as err:          # refused before anything is launched
+                B.invact_sbit_linear_wgrad_ws(kind, dev["yt"], dev["g"], workspace=workspace[:nbytes - 16])
+            assert err.value.status == 5                        # INVACT_ERR_SIZE
+
+
+def test_linear_weight_gradient_splits_by_itself_at_the_mlp_block_shape():
+    """The weight gradient of the 4096 -> 1024 projection of the paper's MLP-block timing, 8192 tokens: 64 tiles of
+    256 x 256, which the library splits four ways; 2^14 sampled outputs against the oracle, and the same bits on a
+    second call that reuses the workspace."""
+    kind, M, N, K = "gelu_erf", 8192, 1024, 4096
+    PT.say(f"invact_sbit_linear_wgrad_ws {kind} M={M} N={N} K={K}, the library's split, sampled")
+    nbytes = B.sbit_linear_wgrad_workspace(M, N, K)
+    assert nbytes == 4 * 64 * 256 * 256 * 4
+    st, v = linear_inputs(kind, M, N, K, 78)
+    dev = {k: PT.to_device(a.reshape(-1), "bf16").view(a.shape) for k, a in st.items()}
+    dec = O.sbit_decode(kind, "bf16", v["yt"].reshape(-1))[1].reshape(M, K)
+    workspace = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    first = B.invact_sbit_linear_wgrad_ws(kind, dev["yt"], dev["g"], workspace=workspace)
+    again = B.invact_sbit_linear_wgrad_ws(kind, dev["yt"], dev["g"], workspace=workspace)
+    torch.cuda.synchronize()
+    assert torch.equal(first, again)
+    gw = PT.to_f64(first.reshape(-1)).reshape(N, K)
+    rng = np.random.default_rng(4)
+    ns, ks = rng.integers(0, N, 128), rng.integers(0, K, 128)
+    ref = O.sbit_linear_wgrad(kind, "bf16", v["yt"][:, ks], v["g"][:, ns])
+    e = product_errors(gw[np.ix_(ns, ks)], ref, np.abs(v["g"][:, ns]).T @ np.abs(dec[:, ks]), M)
+    assert e.max() <= 1.0, e.max()
+
+
 @TILES
 def test_linear_at_a_transformer_block_size_on_sampled_outputs(tile):
     """4096 tokens of a 1024 -> 4096 -> 1024 block (the shape of the paper's MLP-block timing, a batch the oracle
