@@ -194,6 +194,19 @@ int invact_sbit_linear_wgrad_ws(int kind, int dtype, const void* y_tagged, const
                                 void* workspace, size_t workspace_bytes, hipStream_t stream);
 
 /*
+ * invact_sbit_linear_wgrad_ws for callers that cannot allocate a workspace (code under HIP graph capture, serving
+ * loops, harnesses that forbid hipMalloc): the partial sums go to a 64 MiB array that the library's code object
+ * holds on every GPU it is loaded on, until the process ends.  Same arguments, results (bit for bit) and errors as
+ * invact_sbit_linear_wgrad_ws with a workspace of that size; a shape that needs more (possible only with
+ * invact_set_linear_splits) is refused with INVACT_ERR_SIZE.  It allocates and frees nothing.  All calls on one GPU
+ * share the array: calls that may run at the same time on one GPU (different streams, different threads) race
+ * and give wrong results; calls in one stream are ordered and safe.  Nothing in the array has to be cleared
+ * between calls: every element a call reads it has written before.
+ */
+int invact_sbit_linear_wgrad_static(int kind, int dtype, const void* y_tagged, const void* grad_out,
+                                    void* grad_weight, size_t M, size_t N, size_t K, hipStream_t stream);
+
+/*
  * Launch tuning (process-wide, for benchmarking; results are bit-identical
  * whatever is set).  By default a workgroup is one wavefront that handles one
  * tile and retires, and every entry point caps the number of such workgroups

@@ -38,6 +38,7 @@ _PROTOTYPES = {
     "invact_sbit_linear_wgrad": (_int, [_int, _int, _vp, _vp, _vp, _sz, _sz, _sz, _vp]),
     "invact_sbit_linear_wgrad_workspace": (_sz, [_sz, _sz, _sz]),
     "invact_sbit_linear_wgrad_ws": (_int, [_int, _int, _vp, _vp, _vp, _sz, _sz, _sz, _vp, _sz, _vp]),
+    "invact_sbit_linear_wgrad_static": (_int, [_int, _int, _vp, _vp, _vp, _sz, _sz, _sz, _vp]),
     "invact_set_linear_splits": (_int, [_int]),
     "swiglu_invact_fwd": (_int, [_int, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "swiglu_invact_bwd": (_int, [_int, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
@@ -333,4 +334,14 @@ def invact_sbit_linear_wgrad_ws(kind, y_tagged, grad_out, grad_weight=None, work
                                                  grad_weight.data_ptr(), M, N, K,
                                                  None if workspace is None else workspace.data_ptr(),
                                                  0 if workspace is None else workspace.numel(), _stream(stream)))
+    return grad_weight
+
+
+def invact_sbit_linear_wgrad_static(kind, y_tagged, grad_out, grad_weight=None, stream=None):
+    """The same product with its partial sums in the library's own per-GPU array: the call allocates nothing
+    (pass grad_weight), and calls that overlap on one GPU race."""
+    dt, M, N, K, grad_weight = _wgrad_args(y_tagged, grad_out, grad_weight)
+    with _on_device(y_tagged.device):
+        _check(lib().invact_sbit_linear_wgrad_static(_kind(kind), dt, y_tagged.data_ptr(), grad_out.data_ptr(),
+                                                     grad_weight.data_ptr(), M, N, K, _stream(stream)))
     return grad_weight

@@ -697,20 +697,49 @@ extern "C" int invact_sbit_linear_fwd(int kind, int dtype, const void* y_tagged,
     }
 }
 
+// Partial sums of invact_sbit_linear_wgrad_static: one array per GPU, allocated with the code object, shared by
+// every call on that GPU.  In host code the name is only a handle; scratch_of_device() asks the runtime for the
+// array's address on the current device, once per device.
+constexpr size_t kScratchBytes = size_t(64) << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
 namespace {
 
+std::atomic<void*> g_scratch_at[64];
+
+int scratch_of_device(void** at)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return INVACT_ERR_HIP;
+    void* p = g_scratch_at[dev].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return INVACT_ERR_HIP;
+        g_scratch_at[dev].store(p, std::memory_order_release);
+    }
+    *at = p;
+    return INVACT_OK;
+}
+
+// workspace: the caller's; or, with in_scratch, this GPU's scratch array (workspace and workspace_bytes are ignored)
 int wgrad_entry(int kind, int dtype, const void* y_tagged, const void* grad_out, void* grad_weight, size_t M, size_t N, size_t K,
-                bool may_split, void* workspace, size_t workspace_bytes, hipStream_t stream)
+                bool may_split, bool in_scratch, void* workspace, size_t workspace_bytes, hipStream_t stream)
 {
     if (int e = check_kind_dtype(kind, dtype)) return e;
     if (M == 0 || M % kStep != 0 || N % 8 != 0 || K % 8 != 0 || !fits(M, K) || !fits(N, K) || !fits(M, N))
         return INVACT_ERR_SIZE;
     if (N == 0 || K == 0) return INVACT_OK;
     const WgradPlan plan = plan_wgrad(M, N, K, may_split);
-    if (plan.bytes > workspace_bytes || plan.tiles * plan.splits > 0x7FFFFFFFu / 8u /* wavefronts of the summing pass */) return INVACT_ERR_SIZE;
-    if (!y_tagged || !grad_out || !grad_weight || (plan.bytes && !workspace)) return INVACT_ERR_NULL;
-    if (!aligned16(y_tagged) || !aligned16(grad_out) || !aligned16(grad_weight) || (plan.bytes && !aligned16(workspace)))
-        return INVACT_ERR_ALIGN;
+    if (plan.bytes > (in_scratch ? kScratchBytes : workspace_bytes) ||
+        plan.tiles * plan.splits > 0x7FFFFFFFu / 8u /* wavefronts of the summing pass */)
+        return INVACT_ERR_SIZE;
+    if (!y_tagged || !grad_out || !grad_weight) return INVACT_ERR_NULL;
+    if (!aligned16(y_tagged) || !aligned16(grad_out) || !aligned16(grad_weight)) return INVACT_ERR_ALIGN;
+    if (plan.bytes && in_scratch) {
+        if (int e = scratch_of_device(&workspace)) return e;
+    } else if (plan.bytes) {
+        if (!workspace) return INVACT_ERR_NULL;
+        if (!aligned16(workspace)) return INVACT_ERR_ALIGN;
+    }
     const uint16_t *a = static_cast<const uint16_t*>(y_tagged), *g = static_cast<const uint16_t*>(grad_out);
     uint16_t* o = static_cast<uint16_t*>(grad_weight);
     float* const partial = static_cast<float*>(workspace);
@@ -727,7 +756,7 @@ int wgrad_entry(int kind, int dtype, const void* y_tagged, const void* grad_out,
 extern "C" int invact_sbit_linear_wgrad(int kind, int dtype, const void* y_tagged, const void* grad_out,
                                         void* grad_weight, size_t M, size_t N, size_t K, hipStream_t stream)
 {
-    return wgrad_entry(kind, dtype, y_tagged, grad_out, grad_weight, M, N, K, false, nullptr, 0, stream);
+    return wgrad_entry(kind, dtype, y_tagged, grad_out, grad_weight, M, N, K, false, false, nullptr, 0, stream);
 }
 
 extern "C" size_t invact_sbit_linear_wgrad_workspace(size_t M, size_t N, size_t K)
@@ -740,7 +769,13 @@ extern "C" int invact_sbit_linear_wgrad_ws(int kind, int dtype, const void* y_ta
                                            void* grad_weight, size_t M, size_t N, size_t K, void* workspace,
                                            size_t workspace_bytes, hipStream_t stream)
 {
-    return wgrad_entry(kind, dtype, y_tagged, grad_out, grad_weight, M, N, K, true, workspace, workspace_bytes, stream);
+    return wgrad_entry(kind, dtype, y_tagged, grad_out, grad_weight, M, N, K, true, false, workspace, workspace_bytes, stream);
+}
+
+extern "C" int invact_sbit_linear_wgrad_static(int kind, int dtype, const void* y_tagged, const void* grad_out,
+                                               void* grad_weight, size_t M, size_t N, size_t K, hipStream_t stream)
+{
+    return wgrad_entry(kind, dtype, y_tagged, grad_out, grad_weight, M, N, K, true, true, nullptr, 0, stream);
 }
 
 // Benchmarking and tests: 0 lets the library choose the shape of the two products above, 2, 3 or 4 forces Small,

@@ -822,7 +822,7 @@ const char* invact_strerror(int status)
     case INVACT_ERR_DTYPE: return "unknown dtype";
     case INVACT_ERR_NULL:  return "null pointer argument";
     case INVACT_ERR_ALIGN: return "pointer not aligned (16 bytes for tensors, 8 for the mask)";
-    case INVACT_ERR_SIZE:  return "element count too large";
+    case INVACT_ERR_SIZE:  return "size not accepted: too large, not the multiple the entry point asks for, or a workspace too small";
     case INVACT_ERR_HIP:   return "HIP runtime error at kernel launch";
     }
     return "unknown status";
