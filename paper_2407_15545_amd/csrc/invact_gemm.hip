@@ -468,8 +468,8 @@ template <int KIND, class S> struct WgradLoader {
 // The contraction can be split: the grid is `splits` x tiles workgroups, workgroup (split, tile) contracts over its
 // share of the M / 64 steps, and with splits > 1 it leaves its binary32 accumulators in `partial` instead of
 // storing the output: chunk split * tiles + tile, inside it wavefront by wavefront, 16-byte piece by piece in the
-// order of the accumulator registers, lane by lane (every store instruction then covers 1 KiB).  wgrad_sum_kernel adds the chunks of a
-// tile in the order of the splits and stores the output.  That is for outputs with too few tiles to fill the
+// order of the accumulator registers, lane by lane (every store instruction then covers 1 KiB).  wgrad_sum_kernel
+// adds the chunks of a tile in the order of the splits and stores the output.  That is for outputs with too few tiles to fill the
 // chip and a long contraction (the weight gradient of a layer that is narrow on both sides).
 template <int TM, int TN>
 __device__ __forceinline__ size_t partial_at(size_t chunk, unsigned waves, unsigned wave, unsigned lane)
@@ -514,35 +514,35 @@ __global__ __launch_bounds__(S::kThreads) void sbit_linear_wgrad_kernel(const ui
                                      lds + wave * (32 * S::TM) * (32 * S::TN + 8));
 }
 
-// Second pass of a split weight gradient: one wavefront per wavefront of the first pass (workgroup tile * waves +
-// wave) adds that wavefront's accumulators over the splits, first split first, and stores them as the first
-// pass would have.
+// Second pass of a split weight gradient: one wavefront per row of 32 x 32 MFMA tiles of a wavefront of the first
+// pass (workgroup (tile * waves + wave) * TM + i) adds those accumulators over the splits, first split first, and
+// stores them as the first pass would have.
 template <class S>
 __global__ __launch_bounds__(64) void wgrad_sum_kernel(const float* partial, uint16_t* grad_w, unsigned N, unsigned K,
                                                        unsigned tiles, unsigned splits)
 {
-    __shared__ __attribute__((aligned(16))) uint16_t staging[(32 * S::TM) * (32 * S::TN + 8)];
+    __shared__ __attribute__((aligned(16))) uint16_t staging[32 * (32 * S::TN + 8)];
     constexpr unsigned kWaves = S::WM * S::WN;
     const unsigned k_tiles = (K + S::kTileN - 1) / S::kTileN;
-    const unsigned tile = blockIdx.x / kWaves, wave = blockIdx.x % kWaves, lane = threadIdx.x;
+    const unsigned i = blockIdx.x % S::TM, wave = blockIdx.x / S::TM % kWaves, tile = blockIdx.x / (S::TM * kWaves);
+    const unsigned lane = threadIdx.x;
     const TileAt at = banded(tile, tiles / k_tiles, k_tiles);
     const unsigned wm = (wave / S::WN) * (32 * S::TM), wn = (wave % S::WN) * (32 * S::TN);
 
-    f32x16 acc[S::TM][S::TN] = {};
+    f32x16 acc[1][S::TN] = {};
+#pragma unroll 4
     for (unsigned split = 0; split < splits; ++split) {
         const float* const from = partial + partial_at<S::TM, S::TN>((size_t)split * tiles + tile, kWaves, wave, lane);
 #pragma unroll
-        for (int i = 0; i < S::TM; ++i)
+        for (int j = 0; j < S::TN; ++j)
 #pragma unroll
-            for (int j = 0; j < S::TN; ++j)
+            for (int g = 0; g < 4; ++g) {
+                const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(from + ((i * S::TN + j) * 4 + g) * 256));
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const f32x4 v = *reinterpret_cast<const f32x4*>(from + ((i * S::TN + j) * 4 + g) * 256);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) acc[i][j][4 * g + e] += v[e];
-                }
+                for (int e = 0; e < 4; ++e) acc[0][j][4 * g + e] += v[e];
+            }
     }
-    store_accumulators<S::TM, S::TN>(acc, grad_w, N, K, at.row * S::kTileM + wm, at.col * S::kTileN + wn, lane, nullptr, staging);
+    store_accumulators<1, S::TN>(acc, grad_w, N, K, at.row * S::kTileM + wm + 32u * i, at.col * S::kTileN + wn, lane, nullptr, staging);
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -650,7 +650,7 @@ int run_wgrad_shape(const WgradPlan& plan, const uint16_t* a, const uint16_t* g,
     if (int e = launch_tiles<sbit_linear_wgrad_kernel<KIND, S>, S>(plan.tiles * splits, stream, a, g, o, m, n, k, splits, partial))
         return e;
     if (splits == 1) return INVACT_OK;
-    wgrad_sum_kernel<S><<<dim3(tiles * S::WM * S::WN), dim3(64), 0, stream>>>(partial, o, n, k, tiles, splits);
+    wgrad_sum_kernel<S><<<dim3(tiles * S::WM * S::WN * S::TM), dim3(64), 0, stream>>>(partial, o, n, k, tiles, splits);
     return hipGetLastError() == hipSuccess ? INVACT_OK : INVACT_ERR_HIP;
 }
 
@@ -730,7 +730,7 @@ int wgrad_entry(int kind, int dtype, const void* y_tagged, const void* grad_out,
     if (N == 0 || K == 0) return INVACT_OK;
     const WgradPlan plan = plan_wgrad(M, N, K, may_split);
     if (plan.bytes > (in_scratch ? kScratchBytes : workspace_bytes) ||
-        plan.tiles * plan.splits > 0x7FFFFFFFu / 8u /* wavefronts of the summing pass */)
+        plan.tiles * plan.splits > 0x7FFFFFFFu / 32u /* workgroups of the summing pass */)
         return INVACT_ERR_SIZE;
     if (!y_tagged || !grad_out || !grad_weight) return INVACT_ERR_NULL;
     if (!aligned16(y_tagged) || !aligned16(grad_out) || !aligned16(grad_weight)) return INVACT_ERR_ALIGN;
