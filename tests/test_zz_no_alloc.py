@@ -53,3 +53,34 @@ def test_static_scratch_refuses_what_does_not_fit():
     finally:
         B.set_linear_tile(0)
         B.set_linear_splits(0)
+
+
+def test_static_scratch_replays_from_a_graph():
+    """What the entry point is for: captured in a HIP graph (both of its kernels, no allocation), replayed on
+    inputs that change between replays, with eager work and synchronisation in between; every replay against
+    the eager result on the same inputs."""
+    kind, M, N, K = "gelu_tanh", 4096, 1024, 1024
+    assert B.sbit_linear_wgrad_workspace(M, N, K) > 0
+    yt, g = tagged_and_gradient(kind, M, N, K, 4300)
+    out = torch.empty((N, K), dtype=torch.bfloat16, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        B.invact_sbit_linear_wgrad_static(kind, yt, g, grad_weight=out)          # warm-up on the capture stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            B.invact_sbit_linear_wgrad_static(kind, yt, g, grad_weight=out)
+    torch.cuda.synchronize()
+    for replay in range(3):
+        PT.say(f"invact_sbit_linear_wgrad_static from a graph, replay {replay}")
+        fresh_yt, fresh_g = tagged_and_gradient(kind, M, N, K, 4310 + 2 * replay)
+        yt.copy_(fresh_yt)
+        g.copy_(fresh_g)
+        out.fill_(7.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        want = B.invact_sbit_linear_wgrad_ws(kind, yt, g)
+        torch.cuda.synchronize()
+        assert torch.equal(out, want), replay
