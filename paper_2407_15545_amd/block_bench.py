@@ -10,7 +10,9 @@ precision-bit InvAct layer in its place (the variants take turns, group by group
                HIP graph (an MI355X needs ~60 us for this size, about what the Python call path of
                one step costs, so the eager figure measures the host), and on 2^28 elements
   linear+act   Linear(2^10 -> 2^10) + nonlinearity, batch 2^15
-  mlp          Linear(2^10 -> 4*2^10) + nonlinearity + Linear(4*2^10 -> 2^10), batch 2^15
+  mlp          Linear(2^10 -> 4*2^10) + nonlinearity + Linear(4*2^10 -> 2^10), batch 2^15; in bfloat16 also
+               with the sign-bit variant, whose activation and second linear layer are one layer with its own
+               products (Section 3.3)
   geglu        act(Linear(2^10 -> 4*2^10)) * Linear(2^10 -> 4*2^10), batch 2^15; for InvAct
                also with the fused gated kernel (one launch for activation and product)
 
@@ -61,6 +63,19 @@ class Mlp(torch.nn.Module):
 
     def forward(self, x):
         return self.fc2(self.act(self.fc1(x)))
+
+
+class MlpSignBit(torch.nn.Module):
+    """The same block with the sign-bit variant (Section 3.3): activation and second linear layer are one layer,
+    whose two products rebuild the activation from the saved f(x) - min f while they load it."""
+
+    def __init__(self, kind):
+        super().__init__()
+        self.fc1 = torch.nn.Linear(DIM, 4 * DIM)
+        self.fc2 = invact_nn.SignBitActLinear(4 * DIM, DIM, kind=kind)
+
+    def forward(self, x):
+        return self.fc2(self.fc1(x))
 
 
 class GeGlu(torch.nn.Module):
@@ -217,12 +232,17 @@ def main():
             if cls is GeGlu:
                 torch.manual_seed(1)
                 modules["fused"] = GeGlu(glu=invact_nn.InvActGLU(kind)).to(device="cuda", dtype=td)
+            if cls is Mlp and dt == "bf16":                      # the fused products are bfloat16 only
+                torch.manual_seed(1)
+                modules["sbit"] = MlpSignBit(kind).to(device="cuda", dtype=td)
             steps = {col: prepare(m, x, graph=name.endswith("graph")) for col, m in modules.items()}
             res = time_steps(steps, args.iters)
             del steps, modules
             base = res["torch"]
             cell = lambda k: f"{res[k]:8.3f} ({100 * (res[k] / base - 1):+6.2f}%)" if k in res else ""
             print(f"{name:26s} {dt:5s} {base:9.3f} {cell('invact'):>18s} {cell('pbit'):>18s} {cell('fused'):>18s}", flush=True)
+            if "sbit" in res:
+                print(f"{'  sign-bit, fused products':26s} {dt:5s} {'':9s} {cell('sbit'):>18s}", flush=True)
             del x
             torch.cuda.empty_cache()
     for which in ("bert", "llama"):
