@@ -76,6 +76,7 @@ def load(path=None):
         "oracle_sbit_bwd": (None, [c_int, _dbl_p, _dbl_p, _dbl_p, c_size]),
         "oracle_sbit_linear": (None, [c_int, c_int, _dbl_p, _dbl_p, ctypes.c_void_p, _dbl_p, c_size, c_size, c_size]),
         "oracle_sbit_linear_wgrad": (None, [c_int, c_int, _dbl_p, _dbl_p, _dbl_p, c_size, c_size, c_size]),
+        "oracle_sbit_linear_dgrad": (None, [c_int, _dbl_p, _dbl_p, _dbl_p, _dbl_p, c_size, c_size, c_size]),
         "oracle_num_threads": (c_int, []),
     }
     for name, (res, args) in protos.items():
@@ -293,6 +294,17 @@ def sbit_linear_wgrad(kind, dtype, y_tagged, grad_out):
     gw = np.empty((N, K))
     lib().oracle_sbit_linear_wgrad(_kind(kind), _dtype(dtype), yt.reshape(-1), g.reshape(-1), gw.reshape(-1), M, N, K)
     return gw
+
+
+def sbit_linear_dgrad(kind, y_tagged, grad_out, weight):
+    """dX = (dOut W) * q(|Y| + C, S) -> [M, K] (unrounded double); y_tagged is [M, K], grad_out [M, N], weight [N, K]"""
+    yt = np.ascontiguousarray(y_tagged, dtype=np.float64); g = np.ascontiguousarray(grad_out, dtype=np.float64)
+    w = np.ascontiguousarray(weight, dtype=np.float64)
+    (M, K), (M2, N), (N2, K2) = yt.shape, g.shape, w.shape
+    assert M == M2 and N == N2 and K == K2
+    gx = np.empty((M, K))
+    lib().oracle_sbit_linear_dgrad(_kind(kind), yt.reshape(-1), g.reshape(-1), w.reshape(-1), gx.reshape(-1), M, N, K)
+    return gx
 
 
 def num_threads():

@@ -44,6 +44,10 @@
  *     at zero, rounded once to the storage dtype, and the sign bit is set on
  *     the stored pattern; the consumer's Y + C is one binary32 addition, and
  *     the backward evaluates q there.
+ *   - Sign-bit listing, gradient of the layer's input: printed as the incoming
+ *     gradient times f'(f^-1(Y + C, S)); the incoming gradient has the shape of
+ *     the linear layer's output, so the factor meant is the gradient at the
+ *     activation's output, dOut W: dX = (dOut W) * q(Y + C, S).
  */
 #include <math.h>
 #include <stddef.h>
@@ -611,6 +615,30 @@ void oracle_sbit_linear_wgrad(int kind, int dtype, const double *y_tagged, const
             for (size_t m = 0; m < M; ++m)
                 acc += grad_out[m * N + n] * oracle_round_scalar(dtype, fabs(y_tagged[m * K + k]) + C);
             grad_w[n * K + k] = acc;
+        }
+}
+
+/* The same listing, backward, the gradient of the layer's input: the gradient that reaches the
+ * activation's output is dOut W (the adjoint of the forward product; the listing prints the factor
+ * as the incoming gradient alone), and the activation's own backward multiplies it by
+ * f'(f^-1(Y + C, S)), i.e. by q as oracle_sbit_bwd evaluates it: dX = (dOut W) * q(Y + C, S).
+ * grad_out is [M][N], w is [N][K], grad_x is [M][K]; plain sums in double, nothing rounded. */
+void oracle_sbit_linear_dgrad(int kind, const double *y_tagged, const double *grad_out, const double *w,
+                              double *grad_x, size_t M, size_t N, size_t K)
+{
+    init_consts();
+    coeff_set c; default_coeffs(&c);
+    double C = fT_f32[kind];
+#pragma omp parallel for schedule(static)
+    for (size_t m = 0; m < M; ++m)
+        for (size_t k = 0; k < K; ++k) {
+            double acc = 0.0;
+            for (size_t n = 0; n < N; ++n)
+                acc += grad_out[m * N + n] * w[n * K + k];
+            double yt = y_tagged[m * K + k];
+            int s = signbit(yt) != 0 && !isnan(yt);
+            double y = oracle_round_scalar(DTYPE_FP32, fabs(yt) + C);
+            grad_x[m * K + k] = acc * q_with(&c, kind, y, s);
         }
 }
 

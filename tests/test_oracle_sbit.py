@@ -133,3 +133,50 @@ def test_linear_consumer_against_a_library_product_and_its_own_adjoint(kind, dty
     c = float(O.round_to(dtype, np.array([0.75]))[0])
     one = O.sbit_decode(kind, dtype, np.array([c]))[1][0]
     assert np.allclose(O.sbit_linear(kind, dtype, np.full((3, K), -c), np.ones((2, K))), K * one, rtol=1e-14)
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("kind", KINDS)
+def test_linear_consumer_input_gradient(kind, dtype):
+    """dX = (dOut W) * q(|Y| + C, S): reduces to the activation's own backward, agrees with a library product,
+    is the adjoint of the forward product once q is divided out, and is the derivative of the layer."""
+    yt, w, g, _ = linear_case(kind, dtype)
+    (M, K), N = yt.shape, w.shape[0]
+    gx = O.sbit_linear_dgrad(kind, yt, g, w)
+    # the identity as weight leaves the backward of the activation alone
+    gy = (np.arange(M * K) % 7 - 3.0).reshape(M, K)
+    assert np.array_equal(O.sbit_linear_dgrad(kind, yt, gy, np.eye(K)), O.sbit_bwd(kind, yt.reshape(-1), gy.reshape(-1)).reshape(M, K))
+    # numpy's matmul for the product, the pinned element-wise backward for the rest (N != K: a transposed
+    # operand does not even have the shape)
+    assert np.allclose(gx, O.sbit_bwd(kind, yt.reshape(-1), (g @ w).reshape(-1)).reshape(M, K), rtol=1e-13, atol=1e-13)
+    # adjoint of the forward product: <dX / q, Z> = <dOut, Z W^T> for any Z
+    q = O.sbit_bwd(kind, yt.reshape(-1), np.ones(M * K)).reshape(M, K)
+    z = np.random.default_rng(8).standard_normal((M, K))
+    ok = np.abs(q) > 1e-3
+    lhs = np.sum(np.where(ok, gx / np.where(ok, q, 1.0), (g @ w)) * z)
+    rhs = np.sum(g * (z @ w.T))
+    assert abs(lhs - rhs) <= 1e-10 * max(1.0, abs(rhs))
+    # a one-hot dOut picks a row of the weight
+    one = np.zeros((M, N)); one[3, 5] = 2.0
+    picked = O.sbit_linear_dgrad(kind, yt, one, w)
+    assert np.array_equal(picked[3], 2.0 * w[5] * q[3]) and np.count_nonzero(np.delete(picked, 3, 0)) == 0
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_linear_consumer_input_gradient_is_the_derivative_of_the_layer(kind):
+    """Central differences of L(x) = <R, f(x) W^T> with the exact f: dL/dx = f'(x) * (R W), which the oracle's
+    dX reproduces up to the approximation error of q and the rounding of the saved tensor."""
+    rng = np.random.default_rng(12)
+    M, N, K = 9, 7, 11
+    x = synth.storage_to_f64(synth.to_storage((rng.standard_normal(M * K) * 2.0).astype(np.float32), "fp32"), "fp32")
+    w, r = rng.standard_normal((N, K)), rng.standard_normal((M, N))
+    loss = lambda xs: np.sum(r * (O.f(kind, xs).reshape(M, K) @ w.T))
+    h = 1e-6
+    numeric = np.empty(M * K)
+    for i in range(M * K):
+        e = np.zeros(M * K); e[i] = h
+        numeric[i] = (loss(x + e) - loss(x - e)) / (2 * h)
+    _, yt = O.sbit_fwd(kind, "fp32", x)
+    gx = O.sbit_linear_dgrad(kind, yt.reshape(M, K), r, w).reshape(-1)
+    assert np.max(np.abs(gx - numeric)) <= 2e-2 * np.max(np.abs(r @ w))
+    assert np.max(np.abs(gx - numeric)) > 0            # q is an approximation: an exact match would mean f' was used
