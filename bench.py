@@ -207,7 +207,8 @@ def entry_sweep(args):
 
 def consumer_timing(args):
     """The sign-bit variant's consumer: the fused products against invact_sbit_decode followed by torch's GEMM
-    (hipBLASLt / rocBLAS), and torch's GEMM alone on an already decoded activation.  One line per shape M,N,K."""
+    (hipBLASLt / rocBLAS; for the input gradient: torch's GEMM followed by invact_sbit_bwd), and torch's GEMM
+    alone.  One line per product and shape M,N,K."""
     import torch
     from paper_2407_15545_amd import binding as B
     torch.cuda.set_device(0)
@@ -238,6 +239,11 @@ def consumer_timing(args):
                    lambda: torch.mm(g.t(), B.invact_sbit_decode(kind, yt.view(-1), y=tmp.view(-1)).view(M, K), out=gw),
                    lambda: torch.mm(g.t(), y, out=gw)),
         }
+        if N % 64 == 0 and K % 8 == 0:       # the input gradient; its comparison is torch's GEMM + invact_sbit_bwd
+            gx, gy = torch.empty_like(yt), torch.empty_like(yt)
+            cases["dX"] = (lambda: B.invact_sbit_linear_dgrad(kind, yt, g, w, grad_x=gx),
+                           lambda: B.invact_sbit_bwd(kind, yt.view(-1), torch.mm(g, w, out=gy).view(-1), grad_x=gx.view(-1)),
+                           lambda: torch.mm(g, w, out=gy))
         compared = set()                                       # the two comparisons are timed once per product
         for tile in args.linear_tile:
             B.set_linear_tile(tile)

@@ -175,6 +175,21 @@ int invact_sbit_linear_wgrad(int kind, int dtype, const void* y_tagged, const vo
                              void* grad_weight, size_t M, size_t N, size_t K, hipStream_t stream);
 
 /*
+ * Sign-bit variant, the layer's input gradient (Section 3.3, the last product of its listing, read as the
+ * gradient at the activation's output, dOut W, times f'(f^-1(Y + C, S))):
+ *   grad_x[m][k] = (sum_n grad_out[m][n] * weight[n][k]) * q(|y_tagged[m][k]| + C, sign bit of y_tagged[m][k])
+ * One kernel: the product on the matrix units with binary32 accumulation, then every accumulator times q,
+ * evaluated exactly as invact_sbit_bwd evaluates it, then one rounding to bfloat16.  Against a library GEMM
+ * followed by invact_sbit_bwd the M x K product dOut W is never written to memory or rounded.
+ * y_tagged: in, M x K.  grad_out: in, M x N.  weight: in, N x K.  grad_x: out, M x K.  All row-major and dense,
+ * bfloat16 only (INVACT_ERR_DTYPE otherwise).  N must be a multiple of 64 and K a multiple of 8, every matrix must
+ * hold fewer than 2^31 elements (INVACT_ERR_SIZE otherwise; an output with no elements succeeds without a launch).
+ * Matrix pointers must be 16-byte aligned.  grad_x may not alias an input.
+ */
+int invact_sbit_linear_dgrad(int kind, int dtype, const void* y_tagged, const void* grad_out, const void* weight,
+                             void* grad_x, size_t M, size_t N, size_t K, hipStream_t stream);
+
+/*
  * The same weight gradient, allowed to split its contraction (same passage: the sum over the batch of
  * dOut^T (Y + C)).  A narrow layer has a small N x K output and a long sum over M: too few output tiles to
  * occupy the chip.  This entry point then cuts the sum over M into parts, has each part's workgroups leave binary32
@@ -221,7 +236,7 @@ int invact_sbit_linear_wgrad_static(int kind, int dtype, const void* y_tagged, c
  */
 int invact_set_resident_blocks(int blocks);
 int invact_set_blocks_per_cu(int blocks_per_cu);
-/* The two invact_sbit_linear_* products choose their workgroup shape by the size of the output (a 256 x 256 tile
+/* The invact_sbit_linear_* products choose their workgroup shape by the size of the output (a 256 x 256 tile
  * where that still gives every compute unit a workgroup, 128 x 128 otherwise, with 8 wavefronts where a compute
  * unit gets one such tile at most and 4 where it gets more): t = 4, 3 or 2 forces the first, second or third,
  * 0 restores the choice.  Returns its argument, or a negative number if it is none of these. */

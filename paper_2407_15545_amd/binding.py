@@ -36,6 +36,7 @@ _PROTOTYPES = {
     "invact_sbit_bwd": (_int, [_int, _int, _vp, _vp, _vp, _sz, _vp]),
     "invact_sbit_linear_fwd": (_int, [_int, _int, _vp, _vp, _vp, _vp, _sz, _sz, _sz, _vp]),
     "invact_sbit_linear_wgrad": (_int, [_int, _int, _vp, _vp, _vp, _sz, _sz, _sz, _vp]),
+    "invact_sbit_linear_dgrad": (_int, [_int, _int, _vp, _vp, _vp, _vp, _sz, _sz, _sz, _vp]),
     "invact_sbit_linear_wgrad_workspace": (_sz, [_sz, _sz, _sz]),
     "invact_sbit_linear_wgrad_ws": (_int, [_int, _int, _vp, _vp, _vp, _sz, _sz, _sz, _vp, _sz, _vp]),
     "invact_sbit_linear_wgrad_static": (_int, [_int, _int, _vp, _vp, _vp, _sz, _sz, _sz, _vp]),
@@ -345,3 +346,19 @@ def invact_sbit_linear_wgrad_static(kind, y_tagged, grad_out, grad_weight=None, 
         _check(lib().invact_sbit_linear_wgrad_static(_kind(kind), dt, y_tagged.data_ptr(), grad_out.data_ptr(),
                                                      grad_weight.data_ptr(), M, N, K, _stream(stream)))
     return grad_weight
+
+
+def invact_sbit_linear_dgrad(kind, y_tagged, grad_out, weight, grad_x=None, stream=None):
+    """grad_x = (grad_out weight) * q(|y_tagged| + C, sign): y_tagged [M, K], grad_out [M, N], weight [N, K].
+    Returns grad_x [M, K]."""
+    (M, K), (M2, N), (N2, K2) = y_tagged.shape, grad_out.shape, weight.shape
+    if M != M2 or N != N2 or K != K2:
+        raise ValueError("shapes must be y_tagged [M, K], grad_out [M, N], weight [N, K]")
+    grad_x = torch.empty_like(y_tagged) if grad_x is None else grad_x
+    dt = _matrices(y_tagged, grad_out, weight, grad_x)
+    if grad_x.shape != (M, K):
+        raise ValueError("grad_x must be [M, K]")
+    with _on_device(y_tagged.device):
+        _check(lib().invact_sbit_linear_dgrad(_kind(kind), dt, y_tagged.data_ptr(), grad_out.data_ptr(), weight.data_ptr(),
+                                              grad_x.data_ptr(), M, N, K, _stream(stream)))
+    return grad_x

@@ -3,10 +3,13 @@
 // activation rebuilds |Y_tagged| + C first.  The listing does that inside the matrix products,
 //     forward   out = (Y + C) W^T (+ bias)
 //     backward  dW  = dOut^T (Y + C)
-// and so do the two kernels here: bfloat16 MFMA GEMMs (gfx950, v_mfma_f32_32x32x16_bf16, binary32
+//               dX  = (dOut W) * f'(f^-1(Y + C, S))
+// and so do the first two kernels here: bfloat16 MFMA GEMMs (gfx950, v_mfma_f32_32x32x16_bf16, binary32
 // accumulation) whose loader of the activation operand applies |.| + C to every 16-byte piece on its way
 // from global memory to LDS.  The decoded activation never exists in HBM: against invact_sbit_decode
-// followed by a library GEMM that saves one read and one write of the activation per product.
+// followed by a library GEMM that saves one read and one write of the activation per product.  The third
+// product has nothing to decode on the way in; it multiplies its accumulators by q(|Y_tagged| + C, S) on the way
+// out, which saves the write and the read of dOut W that a library GEMM followed by invact_sbit_bwd costs.
 //
 // Shape of both kernels.  A workgroup owns a tile of the output (256 x 256 with 8 wavefronts of 128 x 64, or
 // one of the other shapes below); each wavefront a block of TM x TN MFMA tiles of 32 x 32.  The contraction
@@ -23,6 +26,7 @@
 
 #include "../../include/invact.h"
 #include "invact_constants.h"
+#include "invact_math.h"
 
 namespace {
 
@@ -141,9 +145,9 @@ template <int I, int N, int COUNT> constexpr int share_end = (I + 1) * COUNT / N
 // first fragments of step s + 1.  The steps past the end of the contraction that the pipeline's tail asks for
 // are reloads of the last one and are never multiplied.
 //
-// Two LDS layouts.  Plain: [rows of the tile][kRow], the elements of a row one step of the contraction; a
-// fragment is one 128-bit read per lane (lane l: row l % 32, elements 16 kk + 8 (l / 32) .. + 7).  TRANSPOSED (the
-// weight gradient, whose operands have the contraction index as their slow one): [step of the contraction = 64
+// Two LDS layouts, chosen per operand.  Plain: [rows of the tile][kRow], the elements of a row one step of the contraction; a
+// fragment is one 128-bit read per lane (lane l: row l % 32, elements 16 kk + 8 (l / 32) .. + 7).  TRANSPOSED (an
+// operand that has the contraction index as its slow one: both of the weight gradient, the weight of the input gradient): [step of the contraction = 64
 // rows][rows of the tile + kPadT], as the tiles lie in memory; a fragment is two ds_read_b64_tr_b16 per lane.
 // That instruction transposes inside every group of 16 lanes: lane i of a group receives, as its element j, element
 // i % 4 of the 8 bytes lane i / 4 + 4 j of the group points at.  So lane r of a group points at contraction row
@@ -151,13 +155,13 @@ template <int I, int N, int COUNT> constexpr int share_end = (I + 1) * COUNT / N
 // contraction rows 4 t .. 4 t + 3 of its own tile row: the 8 consecutive ones an MFMA operand wants.
 constexpr unsigned kPadT = 16;          // elements: 4 contraction rows of 32 bytes each then fill all 32 banks once (8: 10 % slower; 24, 32: no faster)
 
-template <class S, bool TRANSPOSED, class Loader>
+template <class S, bool TRANSPOSED_A, bool TRANSPOSED_B, class Loader>
 __device__ __forceinline__ void contract(uint16_t* lds, unsigned steps, unsigned wm, unsigned wn, unsigned lane, Loader& loader,
                                          f32x16 (&acc)[S::TM][S::TN])
 {
     constexpr unsigned kPitchA = S::kTileM + kPadT, kPitchB = S::kTileN + kPadT;   // TRANSPOSED: elements of an LDS row
-    constexpr unsigned kBufA = TRANSPOSED ? kStep * kPitchA : S::kTileM * kRow;    // elements of one buffer
-    constexpr unsigned kBufB = TRANSPOSED ? kStep * kPitchB : S::kTileN * kRow;
+    constexpr unsigned kBufA = TRANSPOSED_A ? kStep * kPitchA : S::kTileM * kRow;  // elements of one buffer
+    constexpr unsigned kBufB = TRANSPOSED_B ? kStep * kPitchB : S::kTileN * kRow;
     static_assert(2 * (kBufA + kBufB) * 2 <= S::kOperandBytes, "both layouts fit the operand buffers");
     constexpr int kMfmas = S::TM * S::TN, kFrags = S::TM + S::TN;
     static_assert(kStep == 64, "four sub-steps");
@@ -172,7 +176,7 @@ __device__ __forceinline__ void contract(uint16_t* lds, unsigned steps, unsigned
         constexpr bool of_a = f == 0 || f > S::TN;
         constexpr int index = f == 0 ? 0 : of_a ? f - S::TN : f - 1;
         bf16x8 v;
-        if constexpr (TRANSPOSED) {
+        if constexpr (of_a ? TRANSPOSED_A : TRANSPOSED_B) {
             typedef short short4_t __attribute__((ext_vector_type(4)));
             typedef __attribute__((address_space(3))) short4_t lds_short4_t;
             constexpr unsigned pitch = of_a ? kPitchA : kPitchB;
@@ -367,7 +371,7 @@ __global__ __launch_bounds__(S::kThreads) void sbit_linear_kernel(const uint16_t
 
     f32x16 acc[S::TM][S::TN] = {};
     LinearLoader<KIND, S> loader(y_tagged, w, M, N, K, m0, n0, t);
-    contract<S, false>(lds, K / kStep, wm, wn, lane, loader, acc);
+    contract<S, false, false>(lds, K / kStep, wm, wn, lane, loader, acc);
 
     // The operand buffers are free once every wavefront is here: each wavefront stages its block of the output in
     // its own part of them; the tile's share of the bias sits behind, as binary32.
@@ -495,7 +499,7 @@ __global__ __launch_bounds__(S::kThreads) void sbit_linear_wgrad_kernel(const ui
 
     f32x16 acc[S::TM][S::TN] = {};
     WgradLoader<KIND, S> loader(y_tagged, grad_out, M, N, K, n0, k0, first_step, steps, t);
-    contract<S, true>(lds, steps, wm, wn, lane, loader, acc);
+    contract<S, true, true>(lds, steps, wm, wn, lane, loader, acc);
 
     if (splits > 1) {
         float* const to = partial + partial_at<S::TM, S::TN>(chunk, S::WM * S::WN, wave, lane);
@@ -543,6 +547,139 @@ __global__ __launch_bounds__(64) void wgrad_sum_kernel(const float* partial, uin
             }
     }
     store_accumulators<1, S::TN>(acc, grad_w, N, K, at.row * S::kTileM + wm + 32u * i, at.col * S::kTileN + wn, lane, nullptr, staging);
+}
+
+// Loader of the input-gradient product dOut W.  dOut [M][N] has the contraction index n as its fast one and is
+// staged like the forward's operands (8 threads per 128-byte row of a step, plain layout); the weight [N][K] has
+// it as its slow one and is staged as it lies in memory, like the weight gradient's operands (transposed
+// layout).  Nothing is decoded: the tasks are LDS writes and reloads, dOut in the first two sub-steps, the
+// weight in the third.  K is a multiple of 8, so a piece of the weight is inside the matrix or outside.
+template <class S> struct DgradLoader {
+    static constexpr unsigned kRowsPerPassA = S::kThreads / 8, kPassesA = S::kTileM / kRowsPerPassA;
+    static constexpr unsigned kPiecesB = S::kTileN / 8, kRowsB = S::kThreads / kPiecesB, kPassesB = kStep / kRowsB;
+    static_assert(kPassesB * kRowsB == kStep && kPassesA % 2 == 0, "whole passes; dOut is staged in two halves");
+    static constexpr unsigned kPitchB = S::kTileN + kPadT;
+    static constexpr int kTasks0 = kPassesA / 2, kTasks1 = kPassesA / 2, kTasks2 = kPassesB;
+
+    __amdgpu_buffer_rsrc_t a_src, b_src;
+    unsigned a_off[kPassesA], b_off[kPassesB];        // byte offsets of this thread's pieces at step 0
+    unsigned a_wr, b_wr;                              // where this thread writes inside a buffer (elements)
+    unsigned b_step, steps;                           // bytes from one step of the weight to the next
+    u32x4 ra[kPassesA], rb[kPassesB];
+
+    __device__ __forceinline__ DgradLoader(const uint16_t* grad_out, const uint16_t* w, unsigned M, unsigned N, unsigned K,
+                                           unsigned m0, unsigned k0, unsigned t)
+        : a_src(whole_buffer(grad_out, M * N * 2u)), b_src(whole_buffer(w, N * K * 2u)), b_step(kStep * K * 2u), steps(N / kStep)
+    {
+        const unsigned r = t >> 3, piece = t & 7u, row_b = t / kPiecesB, piece_b = t % kPiecesB;
+        a_wr = r * kRow + piece * 8u;
+        b_wr = row_b * kPitchB + piece_b * 8u;
+        const bool b_in = k0 + piece_b * 8u < K;
+#pragma unroll
+        for (unsigned p = 0; p < kPassesA; ++p)
+            a_off[p] = m0 + r + kRowsPerPassA * p < M ? ((m0 + r + kRowsPerPassA * p) * N + piece * 8u) * 2u : kOutside;
+#pragma unroll
+        for (unsigned p = 0; p < kPassesB; ++p) b_off[p] = b_in ? ((row_b + kRowsB * p) * K + k0 + piece_b * 8u) * 2u : kOutside;
+    }
+    __device__ __forceinline__ unsigned clamped(unsigned step) const { return step < steps ? step : steps - 1; }
+    __device__ __forceinline__ void load_a(unsigned p, unsigned step)
+    {
+        ra[p] = __builtin_amdgcn_raw_buffer_load_b128(a_src, (int)a_off[p], (int)(clamped(step) * (kStep * 2u)), 0);
+    }
+    __device__ __forceinline__ void load_b(unsigned p, unsigned step)
+    {
+        rb[p] = __builtin_amdgcn_raw_buffer_load_b128(b_src, (int)b_off[p], (int)(clamped(step) * b_step), 0);
+    }
+    __device__ __forceinline__ void prologue(uint16_t* a_buf, uint16_t* b_buf)
+    {
+#pragma unroll
+        for (unsigned p = 0; p < kPassesA; ++p) load_a(p, 0);
+#pragma unroll
+        for (unsigned p = 0; p < kPassesB; ++p) load_b(p, 0);
+#pragma unroll
+        for (unsigned p = 0; p < kPassesA; ++p) {
+            *reinterpret_cast<u32x4*>(a_buf + kRowsPerPassA * p * kRow + a_wr) = ra[p];
+            load_a(p, 1);
+        }
+#pragma unroll
+        for (unsigned p = 0; p < kPassesB; ++p) {
+            *reinterpret_cast<u32x4*>(b_buf + kRowsB * p * kPitchB + b_wr) = rb[p];
+            load_b(p, 1);
+        }
+    }
+    template <int KK, int T>
+    __device__ __forceinline__ void task(uint16_t* a_nxt, uint16_t* b_nxt, unsigned step)
+    {
+        if constexpr (KK < 2) {
+            constexpr int p = KK * (kPassesA / 2) + T;
+            *reinterpret_cast<u32x4*>(a_nxt + kRowsPerPassA * p * kRow + a_wr) = ra[p];
+            load_a(p, step);
+        } else {
+            *reinterpret_cast<u32x4*>(b_nxt + kRowsB * T * kPitchB + b_wr) = rb[T];
+            load_b(T, step);
+        }
+    }
+};
+
+// Multiplies a wavefront's accumulators by q(|y_tagged| + C, sign bit of y_tagged) at their own positions
+// (Eqs. (5)-(8), evaluated exactly as invact_sbit_bwd evaluates them).  A lane owns four neighbouring columns
+// of a row (see store_accumulators): one 8-byte load of the saved tensor per four accumulators; cols is a
+// multiple of 8, so the four are inside the matrix or outside, and outside reads as 0 and is never stored.
+template <int KIND, int TM, int TN>
+__device__ __forceinline__ void scale_by_q(f32x16 (&acc)[TM][TN], const uint16_t* y_tagged, unsigned rows, unsigned cols,
+                                           unsigned row0, unsigned col0, unsigned lane)
+{
+    constexpr float C = min_of_kind<KIND>();
+    const __amdgpu_buffer_rsrc_t src = whole_buffer(y_tagged, rows * cols * 2u);
+    const unsigned row = row0 + (lane & 31u), col = col0 + 4u * (lane >> 5);
+    u32x2 v[TM][TN][4];                      // every load is under way before the first value is used
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const unsigned r = row + 32u * i, c = col + 32u * j + 8u * g;
+                v[i][j][g] = __builtin_amdgcn_raw_buffer_load_b64(src, (int)(r < rows && c < cols ? (r * cols + c) * 2u : kOutside), 0, 0);
+            }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t word = v[i][j][g][e / 2];
+                    const float t = __uint_as_float(e % 2 ? word & 0xFFFF0000u : word << 16);
+                    acc[i][j][4 * g + e] = invact_dev::times_q<KIND, invact_dev::FAST>(
+                        acc[i][j][4 * g + e], __builtin_fabsf(t) + C, (__float_as_uint(t) >> 31) != 0);
+                }
+}
+
+// grad_x[M][K] = (grad_out[M][N] * w[N][K]) * q(|y_tagged| + C, S)[M][K]; every matrix row-major, bfloat16; N a
+// multiple of 64, K a multiple of 8.
+template <int KIND, class S>
+__global__ __launch_bounds__(S::kThreads) void sbit_linear_dgrad_kernel(const uint16_t* y_tagged, const uint16_t* grad_out,
+                                                                        const uint16_t* w, uint16_t* grad_x,
+                                                                        unsigned M, unsigned N, unsigned K)
+{
+    extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
+    const unsigned k_tiles = (K + S::kTileN - 1) / S::kTileN;
+    const TileAt at = banded(xcd_contiguous(blockIdx.x, gridDim.x), gridDim.x / k_tiles, k_tiles);
+    const unsigned m0 = at.row * S::kTileM, k0 = at.col * S::kTileN;
+    const unsigned t = threadIdx.x, lane = t & 63u, wave = t >> 6;
+    const unsigned wm = (wave / S::WN) * (32 * S::TM), wn = (wave % S::WN) * (32 * S::TN);
+
+    f32x16 acc[S::TM][S::TN] = {};
+    DgradLoader<S> loader(grad_out, w, M, N, K, m0, k0, t);
+    contract<S, false, true>(lds, N / kStep, wm, wn, lane, loader, acc);
+
+    scale_by_q<KIND, S::TM, S::TN>(acc, y_tagged, M, K, m0 + wm, k0 + wn, lane);
+    __syncthreads();       // the operand buffers are free once every wavefront is here: the output is staged there
+    store_accumulators<S::TM, S::TN>(acc, grad_x, M, K, m0 + wm, k0 + wn, lane, nullptr,
+                                     lds + wave * (32 * S::TM) * (32 * S::TN + 8));
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -600,6 +737,20 @@ int run_linear(const uint16_t* a, const uint16_t* b, const uint16_t* c, uint16_t
         return launch_tiles<sbit_linear_kernel<KIND, Small8>, Small8>(tiles_of<Small8>(m, n), stream, a, b, c, o, m, n, k);
     default:
         return launch_tiles<sbit_linear_kernel<KIND, Small>, Small>(tiles_of<Small>(m, n), stream, a, b, c, o, m, n, k);
+    }
+}
+
+template <int KIND>
+int run_dgrad(const uint16_t* a, const uint16_t* g, const uint16_t* w, uint16_t* o, unsigned m, unsigned n, unsigned k,
+              hipStream_t stream)
+{
+    switch (tile_for(m, k)) {
+    case Tile::kLarge:
+        return launch_tiles<sbit_linear_dgrad_kernel<KIND, Large>, Large>(tiles_of<Large>(m, k), stream, a, g, w, o, m, n, k);
+    case Tile::kSmall8:
+        return launch_tiles<sbit_linear_dgrad_kernel<KIND, Small8>, Small8>(tiles_of<Small8>(m, k), stream, a, g, w, o, m, n, k);
+    default:
+        return launch_tiles<sbit_linear_dgrad_kernel<KIND, Small>, Small>(tiles_of<Small>(m, k), stream, a, g, w, o, m, n, k);
     }
 }
 
@@ -694,6 +845,25 @@ extern "C" int invact_sbit_linear_fwd(int kind, int dtype, const void* y_tagged,
     case INVACT_GELU_TANH: return run_linear<INVACT_GELU_TANH>(a, b, c, o, m, n, k, stream);
     case INVACT_GELU_ERF:  return run_linear<INVACT_GELU_ERF>(a, b, c, o, m, n, k, stream);
     default:               return run_linear<INVACT_SILU>(a, b, c, o, m, n, k, stream);
+    }
+}
+
+extern "C" int invact_sbit_linear_dgrad(int kind, int dtype, const void* y_tagged, const void* grad_out, const void* weight,
+                                        void* grad_x, size_t M, size_t N, size_t K, hipStream_t stream)
+{
+    if (int e = check_kind_dtype(kind, dtype)) return e;
+    if (N == 0 || N % kStep != 0 || K % 8 != 0 || !fits(M, K) || !fits(N, K) || !fits(M, N)) return INVACT_ERR_SIZE;
+    if (M == 0 || K == 0) return INVACT_OK;
+    if (!y_tagged || !grad_out || !weight || !grad_x) return INVACT_ERR_NULL;
+    if (!aligned16(y_tagged) || !aligned16(grad_out) || !aligned16(weight) || !aligned16(grad_x)) return INVACT_ERR_ALIGN;
+    const uint16_t *a = static_cast<const uint16_t*>(y_tagged), *g = static_cast<const uint16_t*>(grad_out),
+                   *w = static_cast<const uint16_t*>(weight);
+    uint16_t* o = static_cast<uint16_t*>(grad_x);
+    const unsigned m = (unsigned)M, n = (unsigned)N, k = (unsigned)K;
+    switch (kind) {
+    case INVACT_GELU_TANH: return run_dgrad<INVACT_GELU_TANH>(a, g, w, o, m, n, k, stream);
+    case INVACT_GELU_ERF:  return run_dgrad<INVACT_GELU_ERF>(a, g, w, o, m, n, k, stream);
+    default:               return run_dgrad<INVACT_SILU>(a, g, w, o, m, n, k, stream);
     }
 }
 

@@ -115,7 +115,7 @@ __device__ __forceinline__ float act_fast(float x)
 // all eight groups of four banks.
 // Every workgroup copies the table from global memory (3712 bytes, L2-resident) into its LDS before its first
 // element: a twentieth of the kernel's time with one wavefront per workgroup, which is why these kernels run four.
-__device__ __attribute__((aligned(16))) const uint32_t g_mills_table[cst::mills_rows * 8] = { INVACT_MILLS_TABLE };
+static __device__ __attribute__((aligned(16))) const uint32_t g_mills_table[cst::mills_rows * 8] = { INVACT_MILLS_TABLE };
 constexpr int kMillsTableBytes = cst::mills_rows * 32;
 constexpr float kMillsClamp = 14.49f;                      // 8 * 14.49 < mills_rows
 

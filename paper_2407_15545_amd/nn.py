@@ -110,13 +110,14 @@ class _SignBitActLinear(torch.autograd.Function):
     """Activation followed by a linear layer, sign-bit variant (Section 3.3 and its listing): the only
     saved activation is f(x) - min f with the indicator in its sign bit.  In bfloat16, with shapes the fused
     products take (in_features a multiple of 64; for the weight gradient a token count that is a multiple of
-    64 and out_features a multiple of 8), f(x) is rebuilt inside the two matrix products and never exists in
-    memory; otherwise invact_sbit_decode rebuilds it for a library GEMM and it is dropped again.  The rebuilt
+    64 and out_features a multiple of 8; for the input gradient out_features a multiple of 64), f(x) is rebuilt
+    inside the matrix products and never exists in memory, and the input gradient is multiplied by q inside its
+    product; otherwise invact_sbit_decode rebuilds f(x) for a library GEMM and it is dropped again.  The rebuilt
     |Y| + C equals f(x) only to an absolute error of about one ulp at |C| (the stored f - C and the sum live on
     the grid of max(|f|, |C|)): near x = 0 it keeps few of f(x)'s own digits, which in bfloat16 is visible."""
 
     @staticmethod
-    def forward(ctx, x, weight, bias, kind):
+    def forward(ctx, x, weight, bias, kind, fused_dgrad=None):
         y_tagged = B.invact_sbit_fwd(kind, _dense(x)).view(-1, weight.shape[1])
         M, K = y_tagged.shape
         w = _dense(weight)
@@ -125,7 +126,7 @@ class _SignBitActLinear(torch.autograd.Function):
             out = B.invact_sbit_linear_fwd(kind, y_tagged, w, b).view(*x.shape[:-1], weight.shape[0])
         else:
             out = torch.nn.functional.linear(B.invact_sbit_decode(kind, y_tagged.view(-1)).view_as(x), weight, bias)
-        ctx.kind, ctx.has_bias = kind, bias is not None
+        ctx.kind, ctx.has_bias, ctx.fused_dgrad = kind, bias is not None, fused_dgrad
         ctx.save_for_backward(y_tagged, weight)
         return out
 
@@ -142,9 +143,17 @@ class _SignBitActLinear(torch.autograd.Function):
         else:
             grad_w = g2.t().mm(B.invact_sbit_decode(ctx.kind, y_tagged.view(-1)).view(M, K))
         grad_b = g2.sum(0) if ctx.has_bias else None
-        grad_y = _dense(g2.mm(weight))
-        grad_x = B.invact_sbit_bwd(ctx.kind, y_tagged.view(-1), grad_y.view(-1)).view(*grad_out.shape[:-1], K)
-        return grad_x, grad_w, grad_b, None
+        # (dOut W) * q in one kernel: no M x K temporary and one rounding fewer.  Its q is evaluated after the
+        # product rather than beside it, so on large inputs it takes 2-11 % longer than the library's GEMM followed
+        # by invact_sbit_bwd: by default it is used up to 2^24 elements, where it is the faster route.
+        fused = ctx.fused_dgrad if ctx.fused_dgrad is not None else M * K <= 1 << 24
+        if fused and y_tagged.dtype == torch.bfloat16 and g2.dtype == torch.bfloat16 and weight.dtype == torch.bfloat16 \
+                and N % 64 == 0 and K % 8 == 0 and M > 0:
+            grad_x = B.invact_sbit_linear_dgrad(ctx.kind, y_tagged, g2, _dense(weight))
+        else:
+            grad_x = B.invact_sbit_bwd(ctx.kind, y_tagged.view(-1), _dense(g2.mm(weight)).view(-1))
+        grad_x = grad_x.view(*grad_out.shape[:-1], K)
+        return grad_x, grad_w, grad_b, None, None
 
 
 def invact(x, kind="gelu_erf", precision_bit=False):
@@ -208,14 +217,17 @@ class SignBitActLinear(torch.nn.Linear):
     """linear(f(x)): an activation and the linear layer after it as ONE layer, the form the sign-bit variant
     needs (the saved tensor is not the activation, so the consumer has to be part of the layer)."""
 
-    def __init__(self, in_features, out_features, bias=True, kind="gelu_erf", device=None, dtype=None):
+    def __init__(self, in_features, out_features, bias=True, kind="gelu_erf", device=None, dtype=None,
+                 fused_input_gradient=None):
+        """fused_input_gradient: True / False forces or forbids the one-kernel input gradient
+        (invact_sbit_linear_dgrad); None uses it where it is the faster route."""
         super().__init__(in_features, out_features, bias=bias, device=device, dtype=dtype)
         if kind not in B.KINDS:
             raise ValueError(f"kind must be one of {sorted(B.KINDS)}")
-        self.kind = kind
+        self.kind, self.fused_input_gradient = kind, fused_input_gradient
 
     def forward(self, x):
-        return _SignBitActLinear.apply(x, self.weight, self.bias, self.kind)
+        return _SignBitActLinear.apply(x, self.weight, self.bias, self.kind, self.fused_input_gradient)
 
 
 def saved_activation_bytes(fn):

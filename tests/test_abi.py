@@ -88,6 +88,14 @@ def test_argument_validation_happens_before_any_launch():
     assert wg(1, 1, a16, None, a16, 128, 128, 64, None) == ERR_NULL
     assert wg(1, 1, a16, a16, odd, 128, 128, 64, None) == ERR_ALIGN
     assert wg(1, 1, a16, a16, a16, 128, 0, 64, None) == OK
+    dg = lib.invact_sbit_linear_dgrad
+    assert dg(1, 1, a16, a16, a16, a16, 128, 100, 64, None) == ERR_SIZE              # N in whole steps of 64
+    assert dg(1, 1, a16, a16, a16, a16, 128, 64, 100, None) == ERR_SIZE              # K a multiple of 8
+    assert dg(1, 0, a16, a16, a16, a16, 128, 64, 64, None) == ERR_DTYPE
+    assert dg(4, 1, a16, a16, a16, a16, 128, 64, 64, None) == ERR_KIND
+    assert dg(1, 1, a16, a16, None, a16, 128, 64, 64, None) == ERR_NULL
+    assert dg(1, 1, a16, a16, a16, a8, 128, 64, 64, None) == ERR_ALIGN
+    assert dg(1, 1, a16, a16, a16, a16, 0, 64, 64, None) == OK
     # the weight gradient that may split its contraction: what it asks for, and what it refuses (host logic only)
     ws, need = lib.invact_sbit_linear_wgrad_ws, lib.invact_sbit_linear_wgrad_workspace
     assert need(8192, 4096, 4096) == 0                           # 256 tiles of 256 x 256: not split

@@ -216,6 +216,11 @@ def test_sign_bit_act_linear_matches_torch_and_saves_one_tensor(kind, shape, dty
     rx, rw, rb = torch.autograd.grad(ref, (x, layer.weight, layer.bias), g)
     for a, b in ((gx, rx), (gw, rw), (gb, rb)):
         assert (a.float() - b.float()).norm() / b.float().norm() < 3e-2
+    for fused in (True, False):                 # the input gradient in one kernel, and as library GEMM + invact_sbit_bwd
+        layer.fused_input_gradient = fused
+        gx2, = torch.autograd.grad(layer(x), (x,), g)
+        assert (gx2.float() - rx.float()).norm() / rx.float().norm() < 3e-2
+    layer.fused_input_gradient = None
     # saved: the tagged tensor (same size as x) and the weight; torch keeps x, f(x) and the weight
     ours = inv.saved_activation_bytes(lambda: layer(x))[0]
     base = inv.saved_activation_bytes(lambda: F.linear(REFS[kind](x), layer.weight, layer.bias))[0]

@@ -235,6 +235,37 @@ def test_linear_weight_gradient_decodes_while_it_loads(kind, tile):
         assert e.max() <= 1.0, (M, N, K, np.unravel_index(np.argmax(e), e.shape), e.max())
 
 
+def dgrad_errors(got, ref, abs_sum, grad_y, terms):
+    """Error of the input-gradient product in units of its tolerance: the product's own (final rounding plus a
+    binary32 sum of `terms` terms in any order, scaled by |q|, which the caller has folded into abs_sum) plus the
+    backward tolerance of q at the scale of the gradient it multiplies (two binary32 ulps at q's scale of 1)."""
+    tol = 2.0 * PT.ulp(ref, "bf16") + (terms + 2) * 2.0 ** -24 * abs_sum + 2.0 * 2.0 ** -23 * np.abs(grad_y)
+    return np.abs(got - ref) / tol
+
+
+@TILES
+@pytest.mark.parametrize("kind", KINDS)
+def test_linear_input_gradient_applies_q_on_the_way_out(kind, tile):
+    for M, N, K in [(128, 64, 128), (256, 192, 384), (200, 128, 136), (72, 320, 264), (1, 64, 8), (130, 64, 8), (300, 64, 272)]:
+        PT.say(f"invact_sbit_linear_dgrad {kind} M={M} N={N} K={K} tile={tile}")
+        st, v = linear_inputs(kind, M, N, K, 970 + K)
+        dev = {k: PT.to_device(a.reshape(-1), "bf16").view(a.shape) for k, a in st.items()}
+        ref = O.sbit_linear_dgrad(kind, v["yt"], v["g"], v["w"])
+        q = np.abs(O.sbit_bwd(kind, v["yt"].reshape(-1), np.ones(M * K)).reshape(M, K))
+        gx = B.invact_sbit_linear_dgrad(kind, dev["yt"], dev["g"], dev["w"])
+        torch.cuda.synchronize()
+        got = PT.to_f64(gx.reshape(-1)).reshape(M, K)
+        e = dgrad_errors(got, ref, (np.abs(v["g"]) @ np.abs(v["w"])) * q, v["g"] @ v["w"], N)
+        assert e.max() <= 1.0, (M, N, K, np.unravel_index(np.argmax(e), e.shape), e.max())
+        # and the two-kernel route it replaces (binary32 product rounded to bfloat16, then invact_sbit_bwd) lands
+        # within two bfloat16 roundings of it
+        gy = (dev["g"].float() @ dev["w"].float()).to(torch.bfloat16)
+        two_step = PT.to_f64(B.invact_sbit_bwd(kind, dev["yt"].view(-1), gy.view(-1))).reshape(M, K)
+        scale = np.abs(v["g"] @ v["w"]) * q
+        assert np.max(np.abs(got - two_step) - (2.0 ** -7 * scale + 4 * PT.ulp(ref, "bf16") +
+                                                (N + 2) * 2.0 ** -23 * (np.abs(v["g"]) @ np.abs(v["w"])) * q)) <= 0
+
+
 @pytest.fixture
 def splits(request):
     """Forces the number of parts invact_sbit_linear_wgrad_ws splits its contraction into (0: the library's choice)."""
@@ -317,4 +348,11 @@ def test_linear_at_a_transformer_block_size_on_sampled_outputs(tile):
     ns, ks = rng.integers(0, N, 128), rng.integers(0, K, 128)
     ref = O.sbit_linear_wgrad(kind, "bf16", v["yt"][:, ks], v["g"][:, ns])
     e = product_errors(gw[np.ix_(ns, ks)], ref, np.abs(v["g"][:, ns]).T @ np.abs(dec[:, ks]), M)
+    assert e.max() <= 1.0, e.max()
+    gx = PT.to_f64(B.invact_sbit_linear_dgrad(kind, dev["yt"], dev["g"], dev["w"]).reshape(-1)).reshape(M, K)
+    torch.cuda.synchronize()
+    rows, ks = rng.integers(0, M, 128), rng.integers(0, K, 128)
+    ref = O.sbit_linear_dgrad(kind, v["yt"][np.ix_(rows, ks)], v["g"][rows], v["w"][:, ks])
+    q = np.abs(O.sbit_bwd(kind, v["yt"][np.ix_(rows, ks)].reshape(-1), np.ones(128 * 128)).reshape(128, 128))
+    e = dgrad_errors(gx[np.ix_(rows, ks)], ref, (np.abs(v["g"][rows]) @ np.abs(v["w"][:, ks])) * q, v["g"][rows] @ v["w"][:, ks], N)
     assert e.max() <= 1.0, e.max()
