@@ -187,7 +187,7 @@ LINEAR_SHAPES = [(128, 128, 64), (256, 384, 192), (200, 136, 128), (72, 264, 320
 
 @pytest.fixture
 def tile(request):
-    """Forces one of the workgroup shapes of the two products (0: the library's own choice)."""
+    """Forces one of the workgroup shapes of the products (0: the library's own choice)."""
     B.set_linear_tile(request.param)
     yield request.param
     B.set_linear_tile(0)
