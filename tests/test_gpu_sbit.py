@@ -266,6 +266,23 @@ def test_linear_input_gradient_applies_q_on_the_way_out(kind, tile):
                                                 (N + 2) * 2.0 ** -23 * (np.abs(v["g"]) @ np.abs(v["w"])) * q)) <= 0
 
 
+def test_linear_input_gradient_keeps_a_nan_of_the_saved_tensor_to_its_own_element():
+    """The saved tensor enters the input gradient through q alone, element by element: a NaN in it makes that one
+    output NaN and no other, and a saved +inf (f(x) overflowed) gives q = 1, as in invact_sbit_bwd."""
+    kind, M, N, K = "gelu_erf", 192, 128, 264
+    PT.say(f"invact_sbit_linear_dgrad {kind} M={M} N={N} K={K}, NaN and inf in the saved tensor")
+    st, v = linear_inputs(kind, M, N, K, 41)
+    for (m, k), bits in (((5, 7), 0x7FC0), ((100, 263), 0xFFC0), ((191, 0), 0x7F80)):
+        st["yt"][m, k] = bits
+    v["yt"] = synth.storage_to_f64(st["yt"].reshape(-1), "bf16").reshape(M, K)
+    dev = {k: PT.to_device(a.reshape(-1), "bf16").view(a.shape) for k, a in st.items()}
+    ref = O.sbit_linear_dgrad(kind, v["yt"], v["g"], v["w"])
+    got = PT.to_f64(B.invact_sbit_linear_dgrad(kind, dev["yt"], dev["g"], dev["w"]).reshape(-1)).reshape(M, K)
+    torch.cuda.synchronize()
+    assert np.array_equal(np.isnan(got), np.isnan(ref)) and np.isnan(got).sum() == 2
+    assert abs(got[191, 0] - (v["g"] @ v["w"])[191, 0]) <= 2.0 * PT.ulp(ref[191, 0], "bf16") + (N + 2) * 2.0 ** -24 * (np.abs(v["g"]) @ np.abs(v["w"]))[191, 0]
+
+
 @pytest.fixture
 def splits(request):
     """Forces the number of parts invact_sbit_linear_wgrad_ws splits its contraction into (0: the library's choice)."""
