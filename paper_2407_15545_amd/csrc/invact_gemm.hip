@@ -11,13 +11,15 @@
 // product has nothing to decode on the way in; it multiplies its accumulators by q(|Y_tagged| + C, S) on the way
 // out, which saves the write and the read of dOut W that a library GEMM followed by invact_sbit_bwd costs.
 //
-// Shape of both kernels.  A workgroup owns a tile of the output (256 x 256 with 8 wavefronts of 128 x 64, or
+// Shape of the three kernels.  A workgroup owns a tile of the output (256 x 256 with 8 wavefronts of 128 x 64, or
 // one of the other shapes below); each wavefront a block of TM x TN MFMA tiles of 32 x 32.  The contraction
 // runs in steps of 64 as a software pipeline of depth two (see contract): operand tiles travel global memory
 // -> registers -> (decode) -> one of two LDS buffers -> MFMA fragments, and the work of all four stages is
 // spread between the MFMAs of a step.  Rows and columns outside the matrices are handled by the buffer
 // extents (loads return 0, stores are dropped).  Workgroup indices are remapped so that the workgroups an XCD
 // receives (every eighth one) are neighbours in the output and share their operand tiles in that XCD's L2.
+// The weight gradient can also split its contraction over a grid of splits x tiles workgroups, which leave
+// binary32 partial tiles in a workspace (the caller's, or a static device array) for a small summing kernel.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
