@@ -261,7 +261,9 @@ __device__ __forceinline__ float act_minus_min_signed(float x)
         v = (float)act_precise<KIND>(x, (double)C);
         v = (v < 0.0f) ? 0.0f : v;
     }
-    return (x < KindConst<KIND>::T) ? -v : v;
+    // |v| = v for every number here; for a NaN it clears the sign the NaN came with, so that the stored sign bit
+    // is the indicator (0 for a NaN) for every input.  A source modifier of the select: no instruction.
+    return (x < KindConst<KIND>::T) ? -v : __builtin_fabsf(v);
 }
 
 // ---------------------------------------------------------------------------

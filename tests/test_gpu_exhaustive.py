@@ -1,8 +1,9 @@
 """Binary32 kernels against the oracle over the whole input space.
 
-Every STRIDE-th binary32 bit pattern goes through invact_fwd (all patterns) and invact_bwd (every stored y
-the backward can meet: y >= f(T) - 2^-12 with s = 0, and y in [f(T) - 2^-12, +0] with s = 1, grad_y = 1), with
-the tolerances of tests/parity.py; the forward's masks must be bit-exact.  STRIDE is 61 by default (7 * 10^7
+Every STRIDE-th binary32 bit pattern goes through invact_fwd, invact_pbit_fwd and invact_sbit_fwd (all patterns)
+and invact_bwd (every stored y the backward can meet: y >= f(T) - 2^-12 with s = 0, and y in [f(T) - 2^-12, +0]
+with s = 1, grad_y = 1), with the tolerances of tests/parity.py; the forward's masks, tag bits and sign bits
+must be exact.  STRIDE is 61 by default (7 * 10^7
 patterns per case, a few seconds); with INVACT_EXHAUSTIVE=1 in the environment it is 1, i.e. all 2^32 patterns
 (2-4 minutes per case):
 
@@ -102,3 +103,54 @@ def test_backward_over_all_binary32_saved_outputs(kind):
     print(f"\nRESULT bwd {kind} stride {STRIDE}: {w.total} cases, worst {w.tol:.4f} of the tolerance at {w.where_tol}, "
           f"worst literal {w.ulp:.4g} ulp at {w.where_ulp} [{time.time() - t0:.0f} s]", flush=True)
     assert w.tol <= 1.0, w.where_tol
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_precision_bit_forward_over_all_binary32_inputs(kind):
+    """invact_pbit_fwd: bit 0 of the stored pattern is the indicator for every input (0 for a NaN), the value
+    within 2 ulp of the oracle's rounded-then-tagged one and within 3 ulp of f(x) itself."""
+    w, bits_ok, t0 = Worst(), True, time.time()
+    for start, count in pattern_blocks(0x00000000, 0xFFFFFFFF):
+        PT.say(f"exhaustive pbit fwd {kind}: patterns from {start:#010x}, {count} of them, stride {STRIDE}")
+        x = patterns_to_device(start, count)
+        y = B.invact_pbit_fwd(kind, x)
+        torch.cuda.synchronize()
+        x64 = x.cpu().numpy().astype(np.float64)
+        ye, ys = O.pbit_fwd(kind, "fp32", x64)
+        tag = y.view(torch.int32).cpu().numpy().view(np.uint32) & 1
+        bits_ok &= bool(np.array_equal(tag, O.indicator(kind, x64).astype(np.uint32)))
+        got = y.cpu().numpy().astype(np.float64)
+        w.update(start, got, ys, PT.forward_errors(got, ys, "fp32"))
+        assert (PT.forward_errors(got, ye, "fp32") * 2).max() <= 3.0
+    print(f"\nRESULT pbit fwd {kind} stride {STRIDE}: {w.total} inputs, worst {w.tol:.4f} of the tolerance at {w.where_tol}, "
+          f"worst literal {w.ulp:.4g} ulp at {w.where_ulp}, tag bits {'exact' if bits_ok else 'DIFFER'} "
+          f"[{time.time() - t0:.0f} s]", flush=True)
+    assert bits_ok
+    assert w.tol <= 1.0, w.where_tol
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_sign_bit_forward_over_all_binary32_inputs(kind):
+    """invact_sbit_fwd: the sign bit of the stored pattern is the indicator for every input, NaNs included (their
+    indicator is 0); the magnitude against the exact f(x) - C with the tolerance of tests/test_gpu_sbit.py."""
+    from test_gpu_sbit import magnitude_errors, sign_bits
+    C = O.fT(kind, f32=True)
+    worst, where, signs_ok, total, t0 = 0.0, None, True, 0, time.time()
+    for start, count in pattern_blocks(0x00000000, 0xFFFFFFFF):
+        PT.say(f"exhaustive sbit fwd {kind}: patterns from {start:#010x}, {count} of them, stride {STRIDE}")
+        x = patterns_to_device(start, count)
+        yt = B.invact_sbit_fwd(kind, x)
+        torch.cuda.synchronize()
+        x64 = x.cpu().numpy().astype(np.float64)
+        ve, _ = O.sbit_fwd(kind, "fp32", x64)
+        signs_ok &= bool(np.array_equal(sign_bits(yt), O.indicator(kind, x64)))
+        got = yt.cpu().numpy().astype(np.float64)
+        err = magnitude_errors(got, ve, O.f(kind, x64), C, "fp32")
+        i = int(np.argmax(err))
+        if err[i] > worst:
+            worst, where = float(err[i]), (hex(start + STRIDE * i), float(got[i]), float(ve[i]))
+        total += count
+    print(f"\nRESULT sbit fwd {kind} stride {STRIDE}: {total} inputs, worst {worst:.4f} of the tolerance at {where}, "
+          f"sign bits {'exact' if signs_ok else 'DIFFER'} [{time.time() - t0:.0f} s]", flush=True)
+    assert signs_ok
+    assert worst <= 1.0, where

@@ -95,8 +95,7 @@ def test_sbit_every_bf16_pattern(kind):
     PT.say(f"invact_sbit_fwd {kind} all bf16 patterns")
     got = B.invact_sbit_fwd(kind, PT.to_device(bits, "bf16"))
     torch.cuda.synchronize()
-    ok = ~np.isnan(x64)
-    assert np.array_equal(sign_bits(got)[ok], O.indicator(kind, x64)[ok])
+    assert np.array_equal(sign_bits(got), O.indicator(kind, x64))           # NaNs included: their indicator is 0
     with np.errstate(invalid="ignore"):
         err = magnitude_errors(PT.to_f64(got), ve, O.f(kind, x64), C, "bf16")
     assert err.max() <= 1.0, PT.worst(err, x64, ve, PT.to_f64(got))
