@@ -89,7 +89,9 @@ int invact_bwd(int kind, int dtype, const void* y, const void* mask,
  * Gated block, forward (Experiments, "GeGLU" block; Limitations: the product
  * saves the activation's output anyway):
  *   act[i] = f(gate[i]),  mask bit i = (gate[i] < T),  h[i] = f(gate[i]) * up[i]
- * (h is formed from the unrounded activation).  The block saves act, up, mask.
+ * (h is formed from the unrounded activation: with binary32 storage in binary64, within 2 ulp for every gate and
+ * up; with bfloat16 storage from the binary32 value, which below 2^-126 may be flushed or underflow gradually, so
+ * that where |f(gate)| < 2^-126 h carries an absolute error of up to 2^-126 |up|).  The block saves act, up, mask.
  * gate, up: in.  act, h: out.  mask: out.
  * swiglu_invact_fwd is geglu_invact_fwd with kind = INVACT_SILU.
  */

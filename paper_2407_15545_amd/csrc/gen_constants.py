@@ -153,14 +153,16 @@ def main():
     out.append("static constexpr float erfcx_fast_p = 0.42f;")
     out.append(arr("erfcx_fast", mono))
     # binary32 storage: erfcx from a table of short polynomials (held in LDS by the kernels): 116 intervals of
-    # width 1/8 cover every |x| whose result is not yet +-0 or x itself in binary32
-    rows, per_unit = 116, 8
+    # width 1/8 cover every |x| whose result is not yet +-0 or x itself in binary32; the gated forward, whose
+    # product f(gate) * up can still be a binary32 number where f(gate) alone no longer is (|up| up to 3.4e38),
+    # uses 160 (beyond x = -20, |x Phi(x)| * 3.4e38 is below half the smallest subnormal)
+    rows, near_rows, per_unit = 160, 116, 8
     table, err = mills_table(rows, per_unit)
     out.append(f"// Phi(-x) exp(x^2/2) on [{0}, {rows / per_unit}): row i = coefficients in t = {per_unit} x - i of a degree-4 fit "
                f"on [i/{per_unit}, (i+1)/{per_unit}); max rel. error {err:.2e}.")
     out.append("// 32-bit words: for every row c0 and c1 as binary64 (low word first); then for every row c2, c3, c4 as binary32")
     out.append("// and one word of padding (two arrays of 16-byte entries).")
-    out.append(f"static constexpr int mills_rows = {rows}, mills_per_unit = {per_unit};")
+    out.append(f"static constexpr int mills_rows = {rows}, mills_rows_near = {near_rows}, mills_per_unit = {per_unit};")
     out.append(f"#define INVACT_MILLS_TABLE \\")
     for i, row in enumerate(table):
         words = struct.unpack("<4I", struct.pack("<dd", row[0], row[1]))

@@ -384,6 +384,7 @@ struct FwdOp {                       // y = f(x), s = [x < T]
     }
     static constexpr int kMask = MASK_WRITE;
     static constexpr bool kMillsTable = KIND == GELU_ERF && S::kPrec == PRECISE   /* erfcx comes from the LDS table */;
+    static constexpr bool kMillsFar = false;
     static constexpr Shape kShape = pick<DT>({2, 32}, {1, 32});   // {tiles, resident cap}: binary32, bfloat16
 };
 
@@ -409,7 +410,7 @@ struct BwdOp {                       // grad_x = grad_y * q(y, s)
         return bit;
     }
     static constexpr int kMask = MASK_READ;
-    static constexpr bool kMillsTable = false;
+    static constexpr bool kMillsTable = false, kMillsFar = false;
     static constexpr Shape kShape = pick<DT>({1, 24}, {1, 32});   // {tiles, resident cap}: binary32, bfloat16
 };
 
@@ -442,6 +443,7 @@ struct GluFwdOp {                    // act = f(gate), s = [gate < T], h = f(gat
     }
     static constexpr int kMask = MASK_WRITE;
     static constexpr bool kMillsTable = KIND == GELU_ERF && S::kPrec == PRECISE   /* erfcx comes from the LDS table */;
+    static constexpr bool kMillsFar = true;       // h = f(gate) * up needs f(gate) where it is far below binary32's range
     // {tiles, resident cap}: binary32, bfloat16; the binary32 erf form has arithmetic enough to want every slot
     static constexpr Shape kShape = pick<DT>({1, kMillsTable ? 32 : 16}, {1, 16});
 };
@@ -476,7 +478,7 @@ struct GluBwdOp {                    // grad_up = grad_h * act ; grad_gate = gra
         return bit;
     }
     static constexpr int kMask = MASK_READ;
-    static constexpr bool kMillsTable = false;
+    static constexpr bool kMillsTable = false, kMillsFar = false;
     static constexpr Shape kShape = pick<DT>({1, 16}, {1, 16});   // {tiles, resident cap}: binary32, bfloat16
 };
 
@@ -502,6 +504,7 @@ struct PbitFwdOp {                   // y = f(x) with bit 0 := [x < T]
     }
     static constexpr int kMask = MASK_NONE;
     static constexpr bool kMillsTable = KIND == GELU_ERF && S::kPrec == PRECISE   /* erfcx comes from the LDS table */;
+    static constexpr bool kMillsFar = false;
     static constexpr Shape kShape = pick<DT>({2, 32}, {1, 32});   // {tiles, resident cap}: binary32, bfloat16
 };
 
@@ -529,7 +532,7 @@ struct PbitBwdOp {                   // s = bit 0 of y; grad_x = grad_y * q(y, s
         return false;
     }
     static constexpr int kMask = MASK_NONE;
-    static constexpr bool kMillsTable = false;
+    static constexpr bool kMillsTable = false, kMillsFar = false;
     static constexpr Shape kShape = pick<DT>({1, 24}, {1, 32});   // {tiles, resident cap}: binary32, bfloat16
 };
 
@@ -555,6 +558,7 @@ struct SbitFwdOp {                   // y_tagged = +-(f(x) - C), sign bit := [x 
     }
     static constexpr int kMask = MASK_NONE;
     static constexpr bool kMillsTable = KIND == GELU_ERF && S::kPrec == PRECISE   /* erfcx comes from the LDS table */;
+    static constexpr bool kMillsFar = false;
     static constexpr Shape kShape = pick<DT>({2, 32}, {1, 32});   // {tiles, resident cap}: binary32, bfloat16
 };
 
@@ -577,7 +581,7 @@ struct SbitDecodeOp {                // y = |y_tagged| + C
         return false;
     }
     static constexpr int kMask = MASK_NONE;
-    static constexpr bool kMillsTable = false;
+    static constexpr bool kMillsTable = false, kMillsFar = false;
     static constexpr Shape kShape = pick<DT>({2, 20}, {1, 32});   // {tiles, resident cap}: binary32, bfloat16
 };
 
@@ -609,7 +613,7 @@ struct SbitBwdOp {                   // s = sign bit of y_tagged; grad_x = grad_
         return false;
     }
     static constexpr int kMask = MASK_NONE;
-    static constexpr bool kMillsTable = false;
+    static constexpr bool kMillsTable = false, kMillsFar = false;
     static constexpr Shape kShape = pick<DT>({1, 24}, {1, 32});   // {tiles, resident cap}: binary32, bfloat16
 };
 
@@ -636,7 +640,7 @@ __global__ __launch_bounds__(kWave * kGroupWaves<Op>) void stream_kernel(const O
     // which wavefront of the grid this is (uniform over the wavefront: make the compiler see it)
     const size_t wave = kWaves == 1 ? (size_t)blockIdx.x
                                     : (size_t)blockIdx.x * kWaves + __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-    if constexpr (Op::kMillsTable) fill_mills_table(threadIdx.x, kWave * kWaves);
+    if constexpr (Op::kMillsTable) fill_mills_table<Op::kMillsFar>(threadIdx.x, kWave * kWaves);
 
     if constexpr (PERSISTENT) {
         const size_t stride = (size_t)gridDim.x * kWaves;
@@ -729,12 +733,12 @@ unsigned occupancy_cap_lds(int resident)
     if (!(prepared.load(std::memory_order_acquire) >> dev & 1)) {
         // what the kernel declares itself (the erfcx table) counts against the same 160 KiB
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(stream_kernel<Op, false>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)(kLdsPerCu - (Op::kMillsTable ? (unsigned)kMillsTableBytes : 0u))) != hipSuccess)
+                                (int)(kLdsPerCu - (Op::kMillsTable ? (unsigned)kMillsTableBytes<Op::kMillsFar> : 0u))) != hipSuccess)
             return 0;
         prepared.fetch_or(uint64_t(1) << dev, std::memory_order_release);
     }
     const unsigned groups = (unsigned)resident / kGroupWaves<Op> ? (unsigned)resident / kGroupWaves<Op> : 1u;
-    const unsigned share = kLdsPerCu / groups, own = Op::kMillsTable ? (unsigned)kMillsTableBytes : 0u;
+    const unsigned share = kLdsPerCu / groups, own = Op::kMillsTable ? (unsigned)kMillsTableBytes<Op::kMillsFar> : 0u;
     return share > own ? share - own : 0;
 }
 

@@ -113,26 +113,34 @@ __device__ __forceinline__ float act_fast(float x)
 // binary32, at the full rate, the rest in binary64); LDS traffic is what this costs, so the row is kept short,
 // and its two halves live in two arrays of 16-byte entries: lanes that read different rows then spread over
 // all eight groups of four banks.
-// Every workgroup copies the table from global memory (3712 bytes, L2-resident) into its LDS before its first
+// Every workgroup copies its part of the table from global memory (3712 or 5120 bytes, L2-resident) into its LDS before its first
 // element: a twentieth of the kernel's time with one wavefront per workgroup, which is why these kernels run four.
+// Two lengths: FAR = false, 116 rows, |x| < 14.5, for the kernels that store f(x) alone; FAR = true, all 160 rows,
+// |x| < 20, for the gated forward, whose product f(gate) * up can still be a binary32 number where f(gate) alone
+// has long rounded to -0 (|up| goes up to 3.4e38; beyond -20 even that product is below half a subnormal).
 static __device__ __attribute__((aligned(16))) const uint32_t g_mills_table[cst::mills_rows * 8] = { INVACT_MILLS_TABLE };
-constexpr int kMillsTableBytes = cst::mills_rows * 32;
-constexpr float kMillsClamp = 14.49f;                      // 8 * 14.49 < mills_rows
+template <bool FAR> constexpr int kMillsRows = FAR ? cst::mills_rows : cst::mills_rows_near;
+template <bool FAR> constexpr int kMillsTableBytes = kMillsRows<FAR> * 32;
+template <bool FAR> constexpr float kMillsClamp = FAR ? 19.99f : 14.49f;          // 8 * clamp < rows
 
 typedef uint32_t mills_piece_t __attribute__((ext_vector_type(4)));      // (c0, c1) or (c2, c3, c4, -) of a row
 
+template <bool FAR>
 __device__ __forceinline__ mills_piece_t* mills_lds()
 {
-    __shared__ mills_piece_t table[cst::mills_rows * 2];
+    __shared__ mills_piece_t table[kMillsRows<FAR> * 2];
     return table;
 }
 
-// The whole workgroup (`threads` of them, `thread` = threadIdx.x) fills the LDS copy.
+// The whole workgroup (`threads` of them, `thread` = threadIdx.x) fills the LDS copy: the first kMillsRows<FAR>
+// entries of either half of the table.
+template <bool FAR>
 __device__ __forceinline__ void fill_mills_table(unsigned thread, unsigned threads)
 {
     const mills_piece_t* src = reinterpret_cast<const mills_piece_t*>(g_mills_table);
-    mills_piece_t* dst = mills_lds();
-    for (unsigned k = thread; k < cst::mills_rows * 2u; k += threads) dst[k] = src[k];
+    mills_piece_t* dst = mills_lds<FAR>();
+    constexpr unsigned R = kMillsRows<FAR>;
+    for (unsigned k = thread; k < 2u * R; k += threads) dst[k] = src[k < R ? k : k - R + cst::mills_rows];
     __syncthreads();
 }
 
@@ -170,7 +178,7 @@ __device__ __forceinline__ double rcp_newton(double d)
 // The clamp drops a NaN; act_precise lets it through by its other operand.
 struct Gate { double P; float xc; };
 
-template <int KIND>
+template <int KIND, bool FAR = false>
 __device__ __forceinline__ Gate gate_precise(float x)
 {
     Gate out;
@@ -187,16 +195,16 @@ __device__ __forceinline__ Gate gate_precise(float x)
     } else {
         // G from the table (see above), times exp(-x^2 / 2).  Beyond the clamp x Phi(-x) rounds to -0 or leaves x
         // as it is, with the clamped P as with the true one.
-        static_assert(kMillsClamp * cst::mills_per_unit < cst::mills_rows, "the clamp keeps the row index inside the table");
-        out.xc = med3(x, -kMillsClamp, kMillsClamp);
+        static_assert(kMillsClamp<FAR> * cst::mills_per_unit < kMillsRows<FAR>, "the clamp keeps the row index inside the table");
+        out.xc = med3(x, -kMillsClamp<FAR>, kMillsClamp<FAR>);
         double xd = (double)out.xc;
         float m = fabsf(out.xc) * (float)cst::mills_per_unit;
-        const mills_piece_t* row = mills_lds() + (unsigned)m;                       // truncation: the interval
+        const mills_piece_t* row = mills_lds<FAR>() + (unsigned)m;                       // truncation: the interval
         const float tf = __builtin_amdgcn_fractf(m);                                // position inside it, exact
         typedef double double2_t __attribute__((ext_vector_type(2)));
         typedef float float4_t __attribute__((ext_vector_type(4)));
         const double2_t lo = __builtin_bit_cast(double2_t, row[0]);                 // c0, c1
-        const float4_t hi = __builtin_bit_cast(float4_t, row[cst::mills_rows]);     // c2, c3, c4, -
+        const float4_t hi = __builtin_bit_cast(float4_t, row[kMillsRows<FAR>]);     // c2, c3, c4, -
         const float q = fmaf(fmaf(hi[2], tf, hi[1]), tf, hi[0]);
         const double t = (double)tf, c0 = lo[0], c1 = lo[1];
         double g = fma(fma((double)q, t, c1), t, c0);
@@ -207,10 +215,10 @@ __device__ __forceinline__ Gate gate_precise(float x)
 
 // f(x) - minus = (max(x, -0) - minus) - |x| P in binary64, one fused multiply-add: what the gated product
 // (minus = 0) and the sign-bit variant (minus = min f) start from.
-template <int KIND>
+template <int KIND, bool FAR = false>
 __device__ __forceinline__ double act_precise(float x, double minus = 0.0)
 {
-    Gate g = gate_precise<KIND>(x);
+    Gate g = gate_precise<KIND, FAR>(x);
     // max(x, -0) as a select, which lets a NaN x through where a maximum would drop it: the result is then a
     // NaN, and a quiet one (the conversions quiet it), so that the precision-bit variant, which rewrites bit 0 of
     // the stored pattern, cannot turn the signalling NaNs 0x7F800001 / 0xFF800001 into infinities
@@ -236,7 +244,7 @@ __device__ __forceinline__ void act_times(float gate, float up, float& a, float&
         a = act_fast<KIND>(gate);
         h = a * up;
     } else {
-        double ad = act_precise<KIND>(gate);
+        double ad = act_precise<KIND, true>(gate);         // the far table: see g_mills_table
         a = (float)ad;
         h = (float)(ad * (double)up);
     }

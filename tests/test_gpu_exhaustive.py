@@ -154,3 +154,60 @@ def test_sign_bit_forward_over_all_binary32_inputs(kind):
           f"sign bits {'exact' if signs_ok else 'DIFFER'} [{time.time() - t0:.0f} s]", flush=True)
     assert signs_ok
     assert worst <= 1.0, where
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_gated_forward_over_all_binary32_gates(kind):
+    """geglu_invact_fwd with every binary32 pattern as the gate; `up` cycles through ordinary, huge, tiny, zero,
+    infinite and NaN values, so that h = f(gate) * up also overflows and underflows.  The stored activation and h
+    against the oracle (2 ulp; h is formed from the unrounded activation), the mask bit for bit."""
+    ups = torch.tensor([1.5, -0.75, 3.0e30, -2.0e-30, 0.0, 1.0, float("inf"), 7.0e-42, -1.0e38, float("nan"),
+                        0.333333343267, -4096.0, 2.0 ** -126], dtype=torch.float32, device="cuda")     # 13: prime to 61 and 64
+    wa, wh, mask_ok, t0 = Worst(), Worst(), True, time.time()
+    for start, count in pattern_blocks(0x00000000, 0xFFFFFFFF):
+        PT.say(f"exhaustive gated fwd {kind}: patterns from {start:#010x}, {count} of them, stride {STRIDE}")
+        gate = patterns_to_device(start, count)
+        up = ups[torch.arange(count, device="cuda") % ups.numel()]
+        act, h, m = B.geglu_invact_fwd(kind, gate, up)
+        torch.cuda.synchronize()
+        g64, u64 = gate.cpu().numpy().astype(np.float64), up.cpu().numpy().astype(np.float64)
+        ae, _, he, m_ref = O.glu_fwd(kind, "fp32", g64, u64)
+        mask_ok &= bool(np.array_equal(m.cpu().numpy(), m_ref))
+        a_got, h_got = act.cpu().numpy().astype(np.float64), h.cpu().numpy().astype(np.float64)
+        wa.update(start, a_got, ae, PT.forward_errors(a_got, ae, "fp32"))
+        # f(gate) is never 0 for a finite gate, but far out it underflows, in the oracle's binary64 at another gate
+        # than in the kernel's arithmetic; times an infinite `up` that is the difference between NaN and an
+        # infinity.  There either answer passes.
+        either = np.isinf(u64) & (np.abs(ae) < 1e-290) & ~np.isnan(g64)
+        with np.errstate(invalid="ignore"):
+            assert np.all(np.isnan(h_got[either]) | (h_got[either] == np.sign(g64[either]) * u64[either]))    # f has its gate's sign
+        err_h = PT.forward_errors(h_got, he, "fp32")
+        err_h[either] = 0.0
+        wh.update(start, np.where(either, he, h_got), he, err_h)
+    print(f"\nRESULT gated fwd {kind} stride {STRIDE}: {wa.total} inputs, activation worst {wa.tol:.4f} of the tolerance at "
+          f"{wa.where_tol}, h worst {wh.tol:.4f} at {wh.where_tol} (literal {wh.ulp:.4g} ulp at {wh.where_ulp}), masks "
+          f"{'bit-exact' if mask_ok else 'DIFFER'} [{time.time() - t0:.0f} s]", flush=True)
+    assert mask_ok
+    assert wa.tol <= 1.0, wa.where_tol
+    assert wh.tol <= 1.0, wh.where_tol
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_sign_bit_decode_over_all_binary32_patterns(kind):
+    """invact_sbit_decode: |y_tagged| + C is one correctly rounded binary32 addition, so every pattern must come back
+    bit for bit as the oracle's rounded sum (NaN for NaN)."""
+    same, total, t0 = True, 0, time.time()
+    for start, count in pattern_blocks(0x00000000, 0xFFFFFFFF):
+        PT.say(f"exhaustive sbit decode {kind}: patterns from {start:#010x}, {count} of them, stride {STRIDE}")
+        yt = patterns_to_device(start, count)
+        y = B.invact_sbit_decode(kind, yt)
+        torch.cuda.synchronize()
+        _, ys = O.sbit_decode(kind, "fp32", yt.cpu().numpy().astype(np.float64))
+        got = y.cpu().numpy()
+        want = ys.astype(np.float32)
+        nan = np.isnan(want)
+        same &= bool(np.array_equal(np.isnan(got), nan) and np.array_equal(got[~nan].view(np.uint32), want[~nan].view(np.uint32)))
+        total += count
+    print(f"\nRESULT sbit decode {kind} stride {STRIDE}: {total} patterns, {'bit-exact' if same else 'DIFFER'} "
+          f"[{time.time() - t0:.0f} s]", flush=True)
+    assert same

@@ -199,6 +199,37 @@ def test_gated_fwd_bwd_match_oracle(kind, dtype):
         assert e4.max() <= 1.0, (n, PT.worst(e4, as_, gh * up, gg_ref, PT.to_f64(gg)))
 
 
+@pytest.mark.parametrize("kind", KINDS)
+def test_gated_fwd_every_bf16_gate_with_ordinary_and_extreme_up(kind):
+    """Every bfloat16 pattern as the gate against sixteen values of `up`, from tiny to 10^38, infinite and NaN.
+    With bfloat16 storage the product is formed from the activation as binary32 holds it, and where |f(gate)| is
+    below 2^-126 that value may be flushed or gradually underflowed (an absolute error of up to 2^-126, allowed for
+    the stored activation too); h inherits it times |up|.  So: 2 ulp of h, or 2^-126 |up| where |f(gate)| < 2^-126;
+    there, an infinite `up` may give NaN (flushed to zero first) or the signed infinity."""
+    ups = synth.to_storage(np.array([1.5, -0.75, 3.0e30, -2.0e-30, 0.0, 1.0, np.inf, 7.0e-40, -1.0e38, np.nan, 0.3333,
+                                     -4096.0, 2.0 ** -126, 1e7, 1e15, -1e22], dtype=np.float32), "bf16")
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    gate_s, up_s = np.repeat(bits, ups.size), np.tile(ups, bits.size)
+    with np.errstate(invalid="ignore"):
+        gate, up = synth.storage_to_f64(gate_s, "bf16"), synth.storage_to_f64(up_s, "bf16")
+    ae, _, he, m_ref = O.glu_fwd(kind, "bf16", gate, up)
+    PT.say(f"geglu fwd {kind} bf16: all gate patterns x {ups.size} values of up")
+    act, h, m = B.geglu_invact_fwd(kind, PT.to_device(gate_s, "bf16"), PT.to_device(up_s, "bf16"))
+    torch.cuda.synchronize()
+    assert np.array_equal(mask_of(m), m_ref)
+    e1 = PT.forward_errors(PT.to_f64(act), ae, "bf16")
+    assert e1.max() <= 1.0, PT.worst(e1, gate, ae, PT.to_f64(act))
+    got = PT.to_f64(h)
+    with np.errstate(invalid="ignore"):
+        tiny = np.abs(ae) < 2.0 ** -126
+        e2 = PT.forward_errors(got, he, "bf16")
+        inherited = tiny & np.isfinite(up) & (np.abs(got - he) <= 2.0 ** -126 * np.abs(up))
+        at_infinity = tiny & np.isinf(up) & (np.isnan(got) | (got == np.sign(gate) * up))
+    e2[inherited | at_infinity] = 0.0
+    assert e2.max() <= 1.0, PT.worst(e2, gate, up, he, got)
+    assert (inherited & (PT.forward_errors(got, he, "bf16") > 1.0)).sum() < 2000          # a narrow band, not a loophole
+
+
 def test_swiglu_entry_points_equal_geglu_with_silu():
     n = 70001
     gate_s, up_s, gh_s = draw(n, 5, "bf16"), draw(n, 6, "bf16", 1.0), draw(n, 7, "bf16", 0.01)
