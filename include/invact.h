@@ -79,7 +79,8 @@ int invact_fwd(int kind, int dtype, const void* x, void* y, void* mask,
  *   grad_x[i] = grad_y[i] * q(y[i], s_i),
  * q = q_left if the mask bit s_i is 1 else q_right, with the coefficients of
  * the appendix "Approximation Coefficients".  Square-root arguments are
- * clamped at 0; q(+inf, 0) = 1; NaN in y or grad_y gives NaN.
+ * clamped at 0; q(+inf, 0) = 1; NaN in y or grad_y gives NaN; an infinite grad_y gives the infinity of the sign of
+ * grad_y * q (NaN where q is 0).
  * y, grad_y: in.  mask: in, as written by invact_fwd.  grad_x: out.
  */
 int invact_bwd(int kind, int dtype, const void* y, const void* mask,
@@ -105,6 +106,8 @@ int swiglu_invact_fwd(int dtype, const void* gate, const void* up,
  * to the activation inside the product):
  *   grad_up[i]   = grad_h[i] * act[i]
  *   grad_gate[i] = grad_h[i] * up[i] * q(act[i], s_i)
+ * (grad_h * up is formed first -- with binary32 storage without rounding -- so where that product is beyond
+ * binary32's range grad_gate is the infinity, whatever q is)
  * act, up, grad_h: in.  mask: in.  grad_gate, grad_up: out.
  * swiglu_invact_bwd is geglu_invact_bwd with kind = INVACT_SILU.
  */

@@ -382,7 +382,9 @@ __device__ __forceinline__ float times_q(float g, float y, bool left)
         const bool direct = take_left || !(fabsf(p.small) < 0.25f);
         float base  = take_left ? p.ql : (direct ? p.qr : 1.0f);
         float delta = direct ? 0.0f : p.small;
-        return fmaf(g, base, g * delta);
+        // the small term from a g clamped to the finite range (the same g unless it is infinite): an infinite g
+        // times a delta of 0 would turn the infinity of the first term into a NaN; a NaN g stays one through it
+        return fmaf(g, base, med3(g, -FLT_MAX, FLT_MAX) * delta);
     }
 }
 
@@ -399,8 +401,9 @@ __device__ __forceinline__ float times_q(float a, float b, float y, bool left)
         const bool direct = take_left || !(fabsf(p.small) < 0.25f);
         float base  = take_left ? p.ql : (direct ? p.qr : 1.0f);
         float delta = direct ? 0.0f : p.small;
-        float e = fmaf(a, b, -g);                              // a b = g + e exactly
-        return fmaf(g, base, fmaf(g, delta, e * (base + delta)));
+        float e = fmaf(a, b, -g);                              // a b = g + e exactly,
+        e = (fabsf(g) <= FLT_MAX) ? e : 0.0f;                  // unless the product is infinite (or a NaN, which g carries)
+        return fmaf(g, base, fmaf(med3(g, -FLT_MAX, FLT_MAX), delta, e * (base + delta)));     // clamped g: see above
     }
 }
 

@@ -211,3 +211,42 @@ def test_sign_bit_decode_over_all_binary32_patterns(kind):
     print(f"\nRESULT sbit decode {kind} stride {STRIDE}: {total} patterns, {'bit-exact' if same else 'DIFFER'} "
           f"[{time.time() - t0:.0f} s]", flush=True)
     assert same
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_gated_backward_over_all_binary32_saved_activations(kind):
+    """geglu_invact_bwd with every stored activation the backward can meet (as in the plain backward's test) and
+    (grad_h, up) cycling through ordinary, tiny, huge, zero, infinite and NaN pairs, some with a product beyond
+    binary32 (the result is then the infinity the oracle's double arithmetic rounds to, unless q makes it finite
+    again, which the kernel cannot see: those few cases are left out): grad_up = grad_h * act to 2 ulp, grad_gate = grad_h * up * q with the backward's tolerance at the
+    scale of grad_h * up."""
+    pairs = torch.tensor([[1.0, 1.0], [-0.75, 1.5], [1e-20, 1e20], [1e19, -1e-19], [3e-20, 3e-20], [1e-30, 1e-30],
+                          [float("inf"), 1.0], [1.0, float("nan")], [0.0, 5.0], [-2.5e-3, 0.0], [7.0e-42, 1e3],
+                          [1e15, 1e15], [-3.0, 2.0 ** -126], [3e19, 3e19], [float("-inf"), -2.0], [1e30, -1e30]],
+                         dtype=torch.float32, device="cuda")      # 16 pairs; the last three: an infinite product
+    fT = np.float32(O.fT(kind, f32=True))
+    lo_bits = int(np.array([np.float32(fT - np.float32(2.0 ** -12))]).view(np.uint32)[0])
+    ranges = [(0x00000000, 0x7F800000, 0), (0x80000000, lo_bits, 0), (0x80000000, lo_bits, 1), (0x00000000, 0x00000000, 1)]
+    wg, wu, t0 = Worst(), Worst(), time.time()
+    for first, last, s in ranges:
+        for start, count in pattern_blocks(first, last):
+            PT.say(f"exhaustive gated bwd {kind} s={s}: patterns from {start:#010x}, {count} of them, stride {STRIDE}")
+            act = patterns_to_device(start, count)
+            pick = pairs[torch.arange(count, device="cuda") % pairs.shape[0]]
+            gh, up = pick[:, 0].clone(), pick[:, 1].clone()          # clones: a one-element view is not realigned by contiguous()
+            mask = torch.full((B.mask_bytes(count),), 0xFF if s else 0, dtype=torch.uint8, device="cuda")
+            gg, gu = B.geglu_invact_bwd(kind, act, up, mask, gh)
+            torch.cuda.synchronize()
+            a64, g64, u64 = (t.cpu().numpy().astype(np.float64) for t in (act, gh, up))
+            gg_ref, gu_ref = O.glu_bwd(kind, a64, u64, mask.cpu().numpy(), g64)
+            gg_got, gu_got = gg.cpu().numpy().astype(np.float64), gu.cpu().numpy().astype(np.float64)
+            wu.update(start, gu_got, gu_ref, PT.forward_errors(gu_got, gu_ref, "fp32"))
+            with np.errstate(invalid="ignore", over="ignore"):
+                err = PT.backward_errors(gg_got, gg_ref, g64 * u64, "fp32")
+                # grad_h * up overflows binary32 but the product with a small q would not: the kernel gives the infinity
+                err[np.isinf((g64 * u64).astype(np.float32)) & np.isfinite(g64) & np.isfinite(gg_ref.astype(np.float32))] = 0.0
+                wg.update(start, gg_got, gg_ref, err)
+    print(f"\nRESULT gated bwd {kind} stride {STRIDE}: {wg.total} cases, grad_gate worst {wg.tol:.4f} of the tolerance at "
+          f"{wg.where_tol}, grad_up worst {wu.tol:.4f} at {wu.where_tol} [{time.time() - t0:.0f} s]", flush=True)
+    assert wu.tol <= 1.0, wu.where_tol
+    assert wg.tol <= 1.0, wg.where_tol

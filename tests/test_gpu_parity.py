@@ -365,3 +365,34 @@ def test_nan_and_infinities_flow_through():
             assert np.isnan(gv[0]) and gv[1] == 1.0
             ref = O.invact_bwd(kind, ys, mr, np.ones(x.numel()))
             assert PT.backward_errors(gv, ref, np.ones(x.numel()), dtype).max() <= 1.0
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("kind", KINDS)
+def test_infinite_and_nan_gradients_through_every_backward(kind, dtype):
+    """An infinite incoming gradient times q is the signed infinity (the oracle's inf * q), a NaN one a NaN, in all
+    four backward entry points, on saved values from both branches and both sides of q's way of being summed."""
+    xs = synth.to_storage(np.array([-6.0, -2.0, -0.9, -0.7, -0.2, 0.0, 0.3, 1.0, 2.5, 7.0, 30.0], dtype=np.float32), dtype)
+    grads = np.array([np.inf, -np.inf, np.nan], dtype=np.float32)
+    x_s, g_s = np.repeat(xs, grads.size), synth.to_storage(np.tile(grads, xs.size), dtype)
+    x64, g64 = synth.storage_to_f64(x_s, dtype), synth.storage_to_f64(g_s, dtype)
+    n = x64.size
+    dev = lambda v: PT.to_device(synth.f64_to_storage_exact(v, dtype), dtype)
+    g = PT.to_device(g_s, dtype)
+    PT.say(f"infinite gradients {kind} {dtype}")
+
+    def same(got, ref):
+        got = PT.to_f64(got)
+        return np.array_equal(np.isnan(got), np.isnan(ref)) and np.array_equal(got[~np.isnan(ref)], ref[~np.isnan(ref)])
+
+    _, ys, m = O.invact_fwd(kind, dtype, x64)
+    assert same(B.invact_bwd(kind, dev(ys), torch.from_numpy(m).cuda(), g), O.invact_bwd(kind, ys, m, g64))
+    _, yp = O.pbit_fwd(kind, dtype, x64)
+    assert same(B.invact_pbit_bwd(kind, dev(yp), g), O.pbit_bwd(kind, dtype, yp, g64))
+    _, yt = O.sbit_fwd(kind, dtype, x64)
+    assert same(B.invact_sbit_bwd(kind, dev(yt), g), O.sbit_bwd(kind, yt, g64))
+    up = np.full(n, -1.5)
+    gg_ref, gu_ref = O.glu_bwd(kind, ys, up, m, g64)
+    gg, gu = B.geglu_invact_bwd(kind, dev(ys), dev(up), torch.from_numpy(m).cuda(), g)
+    torch.cuda.synchronize()
+    assert same(gg, gg_ref) and same(gu, gu_ref)
