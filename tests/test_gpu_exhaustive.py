@@ -1,11 +1,14 @@
 """Binary32 kernels against the oracle over the whole input space.
 
-Every STRIDE-th binary32 bit pattern goes through invact_fwd, invact_pbit_fwd and invact_sbit_fwd (all patterns)
-and invact_bwd (every stored y the backward can meet: y >= f(T) - 2^-12 with s = 0, and y in [f(T) - 2^-12, +0]
-with s = 1, grad_y = 1), with the tolerances of tests/parity.py; the forward's masks, tag bits and sign bits
-must be exact.  STRIDE is 61 by default (7 * 10^7
-patterns per case, a few seconds); with INVACT_EXHAUSTIVE=1 in the environment it is 1, i.e. all 2^32 patterns
-(2-4 minutes per case):
+Every STRIDE-th binary32 bit pattern goes through
+  * invact_fwd, invact_pbit_fwd, invact_sbit_fwd, invact_sbit_decode (all patterns) and geglu_invact_fwd (all
+    patterns as the gate, `up` cycling through ordinary and extreme values);
+  * invact_bwd, invact_pbit_bwd, invact_sbit_bwd with grad_y = 1 and geglu_invact_bwd with ordinary and extreme
+    (grad_h, up) pairs, over every stored y the backward can meet: y >= f(T) - 2^-12 with s = 0, and y in
+    [f(T) - 2^-12, +0] with s = 1;
+with the tolerances of tests/parity.py; masks, tag bits and sign bits must be exact.  STRIDE is 61 by default
+(7 * 10^7 patterns per case, a few seconds); with INVACT_EXHAUSTIVE=1 in the environment it is 1, i.e. all 2^32
+patterns (2-4 minutes per case):
 
     INVACT_EXHAUSTIVE=1 python -m pytest tests/test_gpu_exhaustive.py -m gpu -s
 
@@ -250,3 +253,38 @@ def test_gated_backward_over_all_binary32_saved_activations(kind):
           f"{wg.where_tol}, grad_up worst {wu.tol:.4f} at {wu.where_tol} [{time.time() - t0:.0f} s]", flush=True)
     assert wu.tol <= 1.0, wu.where_tol
     assert wg.tol <= 1.0, wg.where_tol
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_mask_free_backwards_over_all_binary32_saved_values(kind):
+    """invact_pbit_bwd and invact_sbit_bwd over every saved value they can meet, grad_y = 1, against the oracle with
+    the backward's tolerance.  Precision bit: the patterns of the plain backward's test with bit 0 forced to s.
+    Sign bit: magnitude m = y - C with the sign bit as s; s = 0: every m from 0 to +inf, s = 1: m up to -C + 2^-12
+    (saved outputs up to +0 and a little beyond)."""
+    fT = np.float32(O.fT(kind, f32=True))
+    lo_bits = int(np.array([np.float32(fT - np.float32(2.0 ** -12))]).view(np.uint32)[0])
+    top_bits = int(np.array([np.float32(-fT + np.float32(2.0 ** -12))]).view(np.uint32)[0])
+    wp, ws, t0 = Worst(), Worst(), time.time()
+    ones = lambda count: torch.ones(count, dtype=torch.float32, device="cuda")
+    for first, last, s in [(0x00000000, 0x7F800000, 0), (0x80000000, lo_bits, 0), (0x80000000, lo_bits, 1), (0x00000000, 0x00000000, 1)]:
+        for start, count in pattern_blocks(first, last):
+            PT.say(f"exhaustive pbit bwd {kind} s={s}: patterns from {start:#010x}, {count} of them, stride {STRIDE}")
+            y = ((patterns_to_device(start, count).view(torch.int32) & -2) | s).view(torch.float32)
+            gx = B.invact_pbit_bwd(kind, y, ones(count))
+            torch.cuda.synchronize()
+            ref = O.pbit_bwd(kind, "fp32", y.cpu().numpy().astype(np.float64), np.ones(count))
+            got = gx.cpu().numpy().astype(np.float64)
+            wp.update(start, got, ref, PT.backward_errors(got, ref, np.ones(count), "fp32"))
+    for first, last, s in [(0x00000000, 0x7F800000, 0), (0x00000000, top_bits, 1)]:
+        for start, count in pattern_blocks(first, last):
+            PT.say(f"exhaustive sbit bwd {kind} s={s}: magnitudes from {start:#010x}, {count} of them, stride {STRIDE}")
+            yt = (patterns_to_device(start, count).view(torch.int32) | (-0x80000000 if s else 0)).view(torch.float32)
+            gx = B.invact_sbit_bwd(kind, yt, ones(count))
+            torch.cuda.synchronize()
+            ref = O.sbit_bwd(kind, yt.cpu().numpy().astype(np.float64), np.ones(count))
+            got = gx.cpu().numpy().astype(np.float64)
+            ws.update(start, got, ref, PT.backward_errors(got, ref, np.ones(count), "fp32"))
+    print(f"\nRESULT pbit bwd {kind} stride {STRIDE}: {wp.total} cases, worst {wp.tol:.4f} of the tolerance at {wp.where_tol}; "
+          f"sbit bwd: {ws.total} cases, worst {ws.tol:.4f} at {ws.where_tol} [{time.time() - t0:.0f} s]", flush=True)
+    assert wp.tol <= 1.0, wp.where_tol
+    assert ws.tol <= 1.0, ws.where_tol
