@@ -107,7 +107,7 @@ int swiglu_invact_fwd(int dtype, const void* gate, const void* up,
  *   grad_up[i]   = grad_h[i] * act[i]
  *   grad_gate[i] = grad_h[i] * up[i] * q(act[i], s_i)
  * (grad_h * up is formed first -- with binary32 storage without rounding -- so where that product is beyond
- * binary32's range grad_gate is the infinity, whatever q is)
+ * binary32's range grad_gate is the infinity, whatever q is: NaN where q is 0)
  * act, up, grad_h: in.  mask: in.  grad_gate, grad_up: out.
  * swiglu_invact_bwd is geglu_invact_bwd with kind = INVACT_SILU.
  */

@@ -230,6 +230,41 @@ def test_gated_fwd_every_bf16_gate_with_ordinary_and_extreme_up(kind):
     assert (inherited & (PT.forward_errors(got, he, "bf16") > 1.0)).sum() < 2000          # a narrow band, not a loophole
 
 
+@pytest.mark.parametrize("kind", KINDS)
+def test_gated_bwd_every_bf16_activation_both_mask_bits_and_extreme_factors(kind):
+    """All (act, s) pairs with act a bfloat16 pattern, against eight (grad_h, up) pairs from ordinary to infinite
+    and NaN, including one whose product overflows.  grad_up = grad_h * act to 2 ulp; grad_gate = grad_h * up * q
+    with the backward's tolerance (left-branch activations far outside f's range as in the plain backward's test).
+    grad_h * up is formed first: where it overflows the result is the infinity even if q would make it finite."""
+    pairs = synth.to_storage(np.array([[1.0, 1.0], [-0.75, 1.5], [1e-20, 1e20], [3e19, 3e19], [np.inf, -2.0],
+                                       [1.0, np.nan], [0.0, 5.0], [1e-30, 1e-30]], dtype=np.float32).reshape(-1), "bf16").reshape(-1, 2)
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    act_s = np.tile(np.repeat(bits, len(pairs)), 2)
+    gh_s, up_s = np.tile(np.tile(pairs[:, 0], bits.size), 2), np.tile(np.tile(pairs[:, 1], bits.size), 2)
+    s = np.repeat(np.array([0, 1], np.uint8), bits.size * len(pairs))
+    with np.errstate(invalid="ignore"):
+        a64, g64, u64 = (synth.storage_to_f64(v, "bf16") for v in (act_s, gh_s, up_s))
+    m = O.pack(s)
+    gg_ref, gu_ref = O.glu_bwd(kind, a64, u64, m, g64)
+    PT.say(f"geglu_invact_bwd {kind} bf16: all (act, s) pairs x {len(pairs)} (grad_h, up) pairs")
+    gg, gu = B.geglu_invact_bwd(kind, PT.to_device(act_s, "bf16"), PT.to_device(up_s, "bf16"), torch.from_numpy(m).cuda(),
+                                PT.to_device(gh_s, "bf16"))
+    torch.cuda.synchronize()
+    gg_got, gu_got = PT.to_f64(gg), PT.to_f64(gu)
+    e_up = PT.forward_errors(gu_got, gu_ref, "bf16")
+    assert e_up.max() <= 1.0, PT.worst(e_up, g64, a64, gu_ref, gu_got)
+    with np.errstate(invalid="ignore", over="ignore"):
+        # activations f cannot produce: far left-branch ones as in the plain test; below -1 on either branch q is
+        # astronomically large, and times a product that underflowed in binary32 the comparison means nothing
+        strict = ((s == 0) & (a64 >= -1.0)) | (np.abs(a64) <= 1.0) | np.isnan(a64)
+        product = (g64 * u64).astype(np.float32).astype(np.float64)           # as binary32 forms it
+        e_gate = PT.backward_errors(gg_got, gg_ref, g64 * u64, "bf16")
+        overflowed = np.isinf(product) & np.isfinite(g64) & np.isfinite(u64)
+        e_gate[overflowed & np.where(np.isnan(gg_ref) | (gg_ref == 0), np.isnan(gg_got),          # inf * 0 where q is 0
+                                     gg_got == np.sign(gg_ref) * np.inf)] = 0.0
+    assert e_gate[strict].max() <= 1.0, PT.worst(e_gate[strict], a64[strict], g64[strict], u64[strict], gg_ref[strict], gg_got[strict])
+
+
 def test_swiglu_entry_points_equal_geglu_with_silu():
     n = 70001
     gate_s, up_s, gh_s = draw(n, 5, "bf16"), draw(n, 6, "bf16", 1.0), draw(n, 7, "bf16", 0.01)
