@@ -251,7 +251,7 @@ __device__ __forceinline__ void store_accumulators(const f32x16 (&acc)[TM][TN], 
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const unsigned c = col + 32u * j + 8u * g;
-                f32x4 b = {0.0f, 0.0f, 0.0f, 0.0f};
+                f32x4 b = {-0.0f, -0.0f, -0.0f, -0.0f};           // the addend that changes nothing, not even a -0
                 if (addend) b = *reinterpret_cast<const f32x4*>(addend + c);
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
@@ -277,7 +277,7 @@ __device__ __forceinline__ void store_accumulators(const f32x16 (&acc)[TM][TN], 
             for (int q = 0; q < 16; ++q) {
                 const unsigned c = col + 32u * j + 8u * (q / 4) + (q % 4);
                 if (col0 + c >= cols) continue;
-                const float b = addend ? addend[c] : 0.0f;
+                const float b = addend ? addend[c] : -0.0f;
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
                     if (row0 + row + 32u * i < rows)

@@ -234,6 +234,58 @@ def test_linear_weight_gradient_decodes_while_it_loads(kind, tile):
         assert e.max() <= 1.0, (M, N, K, np.unravel_index(np.argmax(e), e.shape), e.max())
 
 
+@TILES
+@pytest.mark.parametrize("kind", KINDS)
+def test_linear_products_with_an_identity_operand_are_the_decode_bit_for_bit(kind, tile):
+    """Every bfloat16 pattern as a saved value, 1024 rows of 64.  Times the identity as weight the forward product
+    is the decoded tensor itself (sums with zeros are exact, and so is the final rounding of a bfloat16 value), and
+    with the identity as dOut so is the weight gradient: both must equal invact_sbit_decode bit for bit.  In the
+    forward the four rows that hold the infinities and NaNs come out as NaN throughout (NaN times 0)."""
+    M, K = 1024, 64
+    PT.say(f"invact_sbit_linear fwd/wgrad {kind} tile={tile}: all bf16 patterns against an identity operand")
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16).reshape(M, K)
+    yt = PT.to_device(bits.reshape(-1), "bf16").view(M, K)
+    eye_k = torch.eye(K, dtype=torch.bfloat16, device="cuda")
+    eye_m = torch.eye(M, dtype=torch.bfloat16, device="cuda")
+    dec = B.invact_sbit_decode(kind, yt.view(-1)).view(M, K)
+    finite_rows = torch.isfinite(dec.float()).all(dim=1)
+    assert int((~finite_rows).sum()) == 4
+    out = B.invact_sbit_linear_fwd(kind, yt, eye_k)
+    torch.cuda.synchronize()
+    assert torch.equal(out[finite_rows].view(torch.int16), dec[finite_rows].view(torch.int16))
+    assert bool(torch.isnan(out[~finite_rows].float()).all())
+    # the weight gradient sums over the rows, so a NaN anywhere would reach every output: those four rows are
+    # left to the forward, and hold zeros here
+    yt_finite = torch.where(finite_rows[:, None], yt, torch.zeros_like(yt))
+    dec_finite = B.invact_sbit_decode(kind, yt_finite.view(-1)).view(M, K)
+    gw = B.invact_sbit_linear_wgrad(kind, yt_finite, eye_m)
+    B.set_linear_splits(4)
+    try:
+        gw_split = B.invact_sbit_linear_wgrad_ws(kind, yt_finite, eye_m)
+    finally:
+        B.set_linear_splits(0)
+    torch.cuda.synchronize()
+    assert torch.equal(gw.view(torch.int16), dec_finite.view(torch.int16))
+    assert torch.equal(gw_split.view(torch.int16), dec_finite.view(torch.int16))
+
+
+@TILES
+@pytest.mark.parametrize("kind", KINDS)
+def test_linear_input_gradient_with_the_identity_as_weight_is_the_elementwise_backward_bit_for_bit(kind, tile):
+    """Every bfloat16 pattern as a saved value: with the identity as weight dOut W is dOut itself, exactly, and the
+    product's epilogue evaluates q as invact_sbit_bwd does, so the two must agree bit for bit (NaN for NaN)."""
+    M, K = 1024, 64
+    PT.say(f"invact_sbit_linear_dgrad {kind} tile={tile}: all bf16 patterns, identity weight")
+    yt = PT.to_device(np.arange(65536, dtype=np.uint32).astype(np.uint16), "bf16").view(M, K)
+    g = PT.to_device(synth.to_storage(synth.normal(M * K, 17, 1.0), "bf16"), "bf16").view(M, K)
+    want = B.invact_sbit_bwd(kind, yt.view(-1), g.view(-1)).view(M, K)
+    got = B.invact_sbit_linear_dgrad(kind, yt, g, torch.eye(K, dtype=torch.bfloat16, device="cuda"))
+    torch.cuda.synchronize()
+    nan = torch.isnan(want.float())
+    assert torch.equal(torch.isnan(got.float()), nan)
+    assert torch.equal(got[~nan].view(torch.int16), want[~nan].view(torch.int16))          # the sign of a zero included
+
+
 def dgrad_errors(got, ref, abs_sum, grad_y, terms):
     """Error of the input-gradient product in units of its tolerance: the product's own (final rounding plus a
     binary32 sum of `terms` terms in any order, scaled by |q|, which the caller has folded into abs_sum) plus the

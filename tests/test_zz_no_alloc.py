@@ -31,9 +31,10 @@ def test_static_scratch_gives_the_bits_of_a_caller_workspace_call_after_call():
         workspace = torch.empty(nbytes, dtype=torch.uint8, device="cuda") if nbytes else None
         want = B.invact_sbit_linear_wgrad_ws(kind, yt, g, workspace=workspace)
         got = torch.full((N, K), float("nan"), dtype=torch.bfloat16, device="cuda")
-        before = torch.cuda.memory_allocated()
+        allocations = lambda: torch.cuda.memory_stats()["allocation.all.allocated"]      # a count that only grows
+        before = allocations()
         B.invact_sbit_linear_wgrad_static(kind, yt, g, grad_weight=got)
-        assert torch.cuda.memory_allocated() == before
+        assert allocations() == before
         torch.cuda.synchronize()
         assert torch.equal(got, want), (M, N, K)
         assert bool(torch.isfinite(got.float()).all())
