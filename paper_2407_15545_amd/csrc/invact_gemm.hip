@@ -155,7 +155,7 @@ template <int I, int N, int COUNT> constexpr int share_end = (I + 1) * COUNT / N
 // i % 4 of the 8 bytes lane i / 4 + 4 j of the group points at.  So lane r of a group points at contraction row
 // 4 t + r / 4 (t = 0, 1: the two reads), tile rows 4 (r % 4) .. + 3 of the group's 16, and lane i ends up with
 // contraction rows 4 t .. 4 t + 3 of its own tile row: the 8 consecutive ones an MFMA operand wants.
-constexpr unsigned kPadT = 16;          // elements: 4 contraction rows of 32 bytes each then fill all 32 banks once (8: 10 % slower; 24, 32: no faster)
+constexpr unsigned kPadT = 16;          // elements: 4 contraction rows of 32 bytes each then fill all 32 banks once (8: 10 % slower; 24 and, for the large tile, 32: no faster, although 32 takes the remaining bank conflicts away)
 
 template <class S, bool TRANSPOSED_A, bool TRANSPOSED_B, class Loader>
 __device__ __forceinline__ void contract(uint16_t* lds, unsigned steps, unsigned wm, unsigned wn, unsigned lane, Loader& loader,
