@@ -1,7 +1,7 @@
 /*
  * libinvact -- Inverted Activations (arXiv 2407.15545) for AMD MI355X (gfx950).
  *
- * C ABI of the element-wise hot path: a GELU / SiLU layer that saves its OUTPUT
+ * C ABI of the hot path: a GELU / SiLU layer that saves its OUTPUT
  * and a 1-bit-per-element branch mask instead of its input, and rebuilds
  * f'(x) in the backward pass from the saved output with the paper's
  * closed-form approximation of f'(f^-1(y)).
@@ -28,7 +28,8 @@
  *   - The return value is an invact_status (0 = success).  n == 0 succeeds
  *     without a launch.  Arguments are validated before anything is enqueued.
  *   - Calls are thread-safe; the library keeps no mutable state apart from the
- *     tuning parameters below.
+ *     tuning parameters below and the per-GPU array of invact_sbit_linear_wgrad_static,
+ *     whose calls must not overlap on one GPU (see there).
  */
 #ifndef INVACT_H
 #define INVACT_H
