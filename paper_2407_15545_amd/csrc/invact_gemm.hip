@@ -803,8 +803,11 @@ int run_wgrad_shape(const WgradPlan& plan, const uint16_t* a, const uint16_t* g,
     if (int e = launch_tiles<sbit_linear_wgrad_kernel<KIND, S>, S>(plan.tiles * splits, stream, a, g, o, m, n, k, splits, partial))
         return e;
     if (splits == 1) return INVACT_OK;
-    wgrad_sum_kernel<S><<<dim3(tiles * S::WM * S::WN * S::TM), dim3(64), 0, stream>>>(partial, o, n, k, tiles, splits);
-    return hipGetLastError() == hipSuccess ? INVACT_OK : INVACT_ERR_HIP;
+    // the launch's own status, not the thread's last-error slot
+    const float* from = partial;
+    void* argv[] = {&from, &o, &n, &k, const_cast<unsigned*>(&tiles), const_cast<unsigned*>(&splits)};
+    return hipLaunchKernel(reinterpret_cast<const void*>(wgrad_sum_kernel<S>), dim3(tiles * S::WM * S::WN * S::TM), dim3(64),
+                           argv, 0, stream) == hipSuccess ? INVACT_OK : INVACT_ERR_HIP;
 }
 
 template <int KIND>
