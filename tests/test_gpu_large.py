@@ -82,6 +82,24 @@ def test_forward_and_backward_beyond_4_gib(dtype, log2n):
         assert np.array_equal(ms.cpu().numpy(), m_ref)
         assert PT.forward_errors(PT.to_f64(ys), ye, dtype).max() <= 1.0
 
+    # the two mask-free variants share the kernels' skeleton; their windows bit for bit as well
+    del y, gx, act, h, gg, gu, mask, gmask
+    PT.say("  precision-bit and sign-bit entry points on the whole tensor")
+    yp = B.invact_pbit_fwd(kind, x)
+    gp = B.invact_pbit_bwd(kind, yp, g)
+    yt = B.invact_sbit_fwd(kind, x)
+    yd = B.invact_sbit_decode(kind, yt)
+    gs_ = B.invact_sbit_bwd(kind, yt, g)
+    torch.cuda.synchronize()
+    for start in windows(n, x.element_size()):
+        xs, gs = window_of(x, start, n), window_of(g, start, n)
+        yps = B.invact_pbit_fwd(kind, xs)
+        yts = B.invact_sbit_fwd(kind, xs)
+        small = [yps, B.invact_pbit_bwd(kind, yps, gs), yts, B.invact_sbit_decode(kind, yts), B.invact_sbit_bwd(kind, yts, gs)]
+        torch.cuda.synchronize()
+        for big, sm in zip([yp, gp, yt, yd, gs_], small):
+            assert torch.equal(window_of(big, start, n).view(torch.uint8), sm.view(torch.uint8)), start
+
 
 def test_products_next_to_their_size_limit():
     """The matrix products address their operands with 32-bit byte offsets, which is why each matrix must hold fewer
