@@ -151,3 +151,24 @@ def test_torch_extension_loads_and_refuses_cpu_tensors():
             nn.invact_glu(torch.randn(8), torch.randn(8), "silu")
     finally:
         nn.set_wiring(previous)
+
+
+def test_linear_tuning_knobs_and_the_workspace_they_imply():
+    """Host logic only: the forced tile and number of splits, their ranges, and the workspace size that follows."""
+    need = B.lib().invact_sbit_linear_wgrad_workspace
+    try:
+        assert B.lib().invact_set_linear_tile(1) < 0 and B.lib().invact_set_linear_tile(5) < 0
+        assert B.lib().invact_set_linear_splits(-1) < 0 and B.lib().invact_set_linear_splits(65) < 0
+        assert B.lib().invact_set_linear_splits(8) == 8
+        assert need(8192, 1024, 4096) == 8 * 64 * 256 * 256 * 4               # the library's tile (large), eight parts
+        assert need(128, 1024, 4096) == 2 * 64 * 256 * 256 * 4                # capped at the number of 64-row steps
+        assert B.lib().invact_set_linear_tile(2) == 2
+        assert need(8192, 1024, 4096) == 8 * 256 * 128 * 128 * 4              # 128 x 128 tiles: 8 x 32 of them
+        assert B.lib().invact_set_linear_splits(1) == 1
+        assert need(8192, 1024, 4096) == 0
+        assert B.lib().invact_set_linear_splits(0) == 0
+        assert need(8192, 1024, 4096) == 0                                    # a forced tile alone: no split
+    finally:
+        assert B.lib().invact_set_linear_tile(0) == 0 and B.lib().invact_set_linear_splits(0) == 0
+    assert need(8192, 1024, 4096) == 4 * 64 * 256 * 256 * 4
+    assert need(4096, 1024, 1024) == 4 * 64 * 128 * 128 * 4                   # too short for large tiles: small ones, four parts
