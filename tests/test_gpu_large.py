@@ -13,6 +13,15 @@ import parity as PT
 from paper_2407_15545_amd import binding as B
 
 pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(autouse=True)
+def give_the_memory_back():
+    """The tests here hold tens of gigabytes; return torch's cached blocks to the device afterwards."""
+    yield
+    torch.cuda.empty_cache()
+
+
 WINDOW = (1 << 20) + 64          # elements; window starts are multiples of 64, so a window owns whole mask words
 
 
