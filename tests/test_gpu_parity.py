@@ -350,8 +350,13 @@ def test_other_stream_and_grid_shapes_give_identical_bits(dtype):
         gx = B.invact_bwd(kind, y, m, g)
         act, h, m2 = B.geglu_invact_fwd(kind, x, up)
         gg, gu = B.geglu_invact_bwd(kind, act, up, m2, g)
+        yp = B.invact_pbit_fwd(kind, x)
+        gp = B.invact_pbit_bwd(kind, yp, g)
+        yt = B.invact_sbit_fwd(kind, x)
+        yd = B.invact_sbit_decode(kind, yt)
+        gs = B.invact_sbit_bwd(kind, yt, g)
         torch.cuda.synchronize()
-        return [y, m, gx, act, h, m2, gg, gu]
+        return [y, m, gx, act, h, m2, gg, gu, yp, gp, yt, yd, gs]
 
     PT.say(f"streams / grid shapes {dtype}")
     ref = run_all()
