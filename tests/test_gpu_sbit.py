@@ -286,6 +286,40 @@ def test_linear_input_gradient_with_the_identity_as_weight_is_the_elementwise_ba
     assert torch.equal(got[~nan].view(torch.int16), want[~nan].view(torch.int16))          # the sign of a zero included
 
 
+@TILES
+def test_linear_products_write_nothing_outside_their_outputs(tile):
+    """Ragged shapes (the last tiles hang over the matrices on both sides): the outputs sit between two guard
+    zones of a larger buffer, and the guards must come back untouched."""
+    kind, pad = "gelu_erf", 4096
+    for M, N, K in [(200, 136, 128), (320, 72, 264), (130, 8, 64), (64, 264, 200)]:
+        PT.say(f"invact_sbit_linear_* guards M={M} N={N} K={K} tile={tile}")
+        st, _ = linear_inputs(kind, M, N, K, 60 + M)
+        dev = {k: PT.to_device(a.reshape(-1), "bf16").view(a.shape) for k, a in st.items()}
+
+        def guarded(rows, cols):
+            buf = torch.full((rows * cols + 2 * pad,), -7.0, dtype=torch.bfloat16, device="cuda")
+            return buf, buf[pad:pad + rows * cols].view(rows, cols)
+
+        calls = []
+        if K % 64 == 0:
+            buf, out = guarded(M, N)
+            B.invact_sbit_linear_fwd(kind, dev["yt"], dev["w"], dev["b"], out=out)
+            calls.append(("fwd", buf, out))
+        if M % 64 == 0 and N % 8 == 0 and K % 8 == 0:
+            buf, gw = guarded(N, K)
+            B.invact_sbit_linear_wgrad(kind, dev["yt"], dev["g"], grad_weight=gw)
+            calls.append(("wgrad", buf, gw))
+        if N % 64 == 0 and K % 8 == 0:
+            buf, gx = guarded(M, K)
+            B.invact_sbit_linear_dgrad(kind, dev["yt"], dev["g"], dev["w"], grad_x=gx)
+            calls.append(("dgrad", buf, gx))
+        torch.cuda.synchronize()
+        assert calls
+        for name, buf, out in calls:
+            assert bool((buf[:pad] == -7.0).all()) and bool((buf[-pad:] == -7.0).all()), (name, M, N, K)
+            assert bool(torch.isfinite(out.float()).all()) and not bool((out == -7.0).all()), (name, M, N, K)
+
+
 def dgrad_errors(got, ref, abs_sum, grad_y, terms):
     """Error of the input-gradient product in units of its tolerance: the product's own (final rounding plus a
     binary32 sum of `terms` terms in any order, scaled by |q|, which the caller has folded into abs_sum) plus the
